@@ -1,0 +1,183 @@
+/*
+ * toolspec.h - C ABI of the MI355X (gfx950) draft-tree verification library.
+ *
+ * The library implements the hot step of schema-aware, retrieval-augmented
+ * speculative decoding for tool calling: candidate drafts (schema-filled
+ * tokens, enumerated alternatives such as tool names, continuations reused from
+ * retrieved past invocations) are packed into one flattened sequence with a
+ * tree-structured attention mask, the target decoder scores all of them in ONE
+ * forward pass over its KV cache, and the longest accepted path is selected
+ * and appended (paper Sec. 4.1 "Task Formulation"; App. A.1 "Parallel
+ * Verification"; Alg. 1, steps PackDraftsAsTree / Verification /
+ * SelectLongestAcceptedPrefix / append).  Drafting itself (FSM, retrieval)
+ * stays with the caller.
+ *
+ * Conventions
+ *  - All pointers are HOST pointers unless a parameter says "device".
+ *  - Every function returns a ts_status (0 = TS_OK, negative = error) and never
+ *    throws; ts_last_error() gives a message for the calling thread's last error.
+ *  - Errors leave committed state (cache length, pending token) untouched.
+ *  - Handles are not thread-safe.  One HIP stream per model; every call that
+ *    returns data to the host has synchronised that stream before returning.
+ *  - Matrices handed to ts_model_load are row-major [out][in] (y = x W^T),
+ *    element type float (dtype 0) or bfloat16 bit patterns (dtype 1).  The
+ *    library copies and re-tiles them on the device; the caller may free its
+ *    buffers as soon as ts_model_load returns.
+ *
+ * Tree conventions (paper App. A.1: drafts are "compacted into a single
+ * flattened sequence" verified under a tree mask; dynamic trees adapt to each
+ * draft's length, so any shape is legal):
+ *  - The root of the tree is the PENDING token: the last emitted token, whose
+ *    K/V are not in the cache yet.  It is not one of the n_nodes draft nodes.
+ *  - parent_idx[i] is -1 (child of the root) or an index in [0, i): parents
+ *    precede children.  0 <= n_nodes <= TS_MAX_NODES.  Duplicate sibling
+ *    tokens are legal.
+ *  - A node sits at position (committed length + depth); it attends to the
+ *    whole committed context, to the root, to its ancestors and to itself.
+ *  - Acceptance is greedy: a node is accepted iff its parent is accepted (the
+ *    root always is) and its token equals the arg-max token of the logits at
+ *    its parent.  The deepest accepted node wins; ties go to the lowest node
+ *    index, equal logits to the lowest token id.  n_nodes = 0 is plain
+ *    autoregressive decoding.
+ */
+#ifndef TOOLSPEC_H
+#define TOOLSPEC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ts_model ts_model; /* opaque; owns device weights, workspace, stream */
+typedef struct ts_kv    ts_kv;    /* opaque; owns one sequence's paged K/V          */
+typedef int32_t ts_status;
+
+enum {
+  TS_OK = 0,
+  TS_ERR_INVALID_ARG  = -1, /* null pointer, bad size, unsupported shape          */
+  TS_ERR_INVALID_TREE = -2, /* parent_idx[i] outside [-1, i), n_nodes out of range */
+  TS_ERR_TOKEN_RANGE  = -3, /* token id outside [0, vocab)                         */
+  TS_ERR_KV_CAPACITY  = -4, /* committed length + tree rows exceed the capacity    */
+  TS_ERR_STATE        = -5, /* no pending token; commit without a fresh verify     */
+  TS_ERR_OOM          = -6, /* device or host allocation failed                    */
+  TS_ERR_DEVICE       = -7  /* a HIP call failed                                   */
+};
+
+enum { TS_DTYPE_F32 = 0, TS_DTYPE_BF16 = 1 };
+enum { TS_MAX_NODES = 64, TS_PAGE_SIZE = 16 };
+
+/* Decoder shape: pre-norm blocks with RMSNorm, rotary embedding (pair (j, j+hd/2)
+ * rotated by pos * rope_theta^(-2j/hd)), grouped-query attention with softmax scale
+ * 1/sqrt(head_dim), SwiGLU feed-forward, no biases, untied embedding / lm_head.
+ * dtype is the storage type of weights and KV cache; TS_DTYPE_BF16 computes with
+ * bf16 MFMA and fp32 accumulation and needs d_model, n_q_heads*head_dim and d_ffn
+ * to be multiples of 128, head_dim 64 or 128; TS_DTYPE_F32 computes in fp32. */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_theta, rms_eps;
+  int32_t dtype;
+} ts_model_config;
+
+/* Host weight pointers.  The per-layer members are arrays of n_layers pointers. */
+typedef struct {
+  const void* embed;        /* [vocab][d_model]                */
+  const void* lm_head;      /* [vocab][d_model]                */
+  const void* norm_f;       /* [d_model]                       */
+  const void* const* wq;    /* [n_q_heads*head_dim][d_model]   */
+  const void* const* wk;    /* [n_kv_heads*head_dim][d_model]  */
+  const void* const* wv;    /* [n_kv_heads*head_dim][d_model]  */
+  const void* const* wo;    /* [d_model][n_q_heads*head_dim]   */
+  const void* const* wg;    /* [d_ffn][d_model]  gate          */
+  const void* const* wu;    /* [d_ffn][d_model]  up            */
+  const void* const* wd;    /* [d_model][d_ffn]  down          */
+  const void* const* norm1; /* [d_model]  pre-attention gain   */
+  const void* const* norm2; /* [d_model]  pre-FFN gain         */
+} ts_weights;
+
+/* Thread-local description of the last error returned to this thread ("" if none). */
+const char* ts_last_error(void);
+
+/* ---- model ------------------------------------------------------------------
+ * The target model M of Alg. 1.  Copies all weights to the current HIP device.
+ * Errors: INVALID_ARG (null, unsupported shape), OOM, DEVICE. */
+ts_status ts_model_load(const ts_model_config* cfg, const ts_weights* host_weights, ts_model** out);
+ts_status ts_model_free(ts_model* m);
+
+/* When enabled, ts_verify also stores the full fp32 logits of every row so that
+ * ts_get_logits can return them (parity checks); off by default because the
+ * arg-max is fused into the lm_head projection and needs no logits in memory. */
+ts_status ts_model_keep_logits(ts_model* m, int32_t enable);
+/* Logits of rows [row0, row0+n_rows) of the most recent verify on this model
+ * (row 0 = root, row i+1 = draft node i; batched calls concatenate sequences).
+ * host_logits: n_rows * vocab floats.  STATE if logits were not kept. */
+ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, float* host_logits);
+
+/* ---- KV cache ---------------------------------------------------------------
+ * One sequence's cache (the K/V of context x and generated output y): pages of
+ * page_size (= 16) positions, addressed through a page table.  capacity_tokens
+ * must cover the context plus the rows of the largest tree (n_nodes + 1).
+ * Starts empty: length 0, no pending token. */
+ts_status ts_kv_alloc(ts_model* m, int32_t capacity_tokens, int32_t page_size, ts_kv** out);
+ts_status ts_kv_free(ts_kv* kv);
+/* Replace the identity page table by a permutation of [0, n_pages) (n_pages =
+ * ceil(capacity/page_size)); only legal while the cache is empty. */
+ts_status ts_kv_set_page_table(ts_kv* kv, const int32_t* phys_page, int32_t n_pages);
+/* Test/bench helpers, needed because this library has no prefill of its own.
+ * k_host / v_host: [n_layers][n_pos][n_kv_heads][head_dim] in the model dtype,
+ * K already rotated.  Import sets the committed length to n_pos. */
+ts_status ts_kv_import(ts_kv* kv, int32_t n_pos, const void* k_host, const void* v_host);
+ts_status ts_kv_export(ts_kv* kv, int32_t pos0, int32_t n_pos, void* k_host, void* v_host);
+ts_status ts_set_pending(ts_kv* kv, int32_t token);   /* root token of the next verify */
+ts_status ts_kv_len(const ts_kv* kv, int32_t* committed_len);
+/* Roll the committed length back to new_len <= current length (drops later
+ * positions, invalidates the last verify result); the caller sets the pending token. */
+ts_status ts_kv_truncate(ts_kv* kv, int32_t new_len);
+
+/* ---- verification (Alg. 1: Verification + SelectLongestAcceptedPrefix) --------
+ * Scores root + n_nodes draft nodes in one forward pass and walks the longest
+ * accepted path.  Pure with respect to committed state: it writes only the tree
+ * slots [len, len + n_nodes] of the cache and may be repeated.
+ *   draft_tokens, parent_idx : n_nodes int32 each (may be NULL when n_nodes = 0)
+ *   accept_len      : out, number of accepted draft tokens l
+ *   accepted_tokens : out, caller buffer of >= n_nodes ints, first l valid
+ *   accepted_nodes  : out, optional (NULL ok), node index of each accepted token
+ *   bonus_token     : out, arg-max token after the last accepted node (or the root)
+ * Tokens emitted by the step = accepted_tokens[0..l) followed by bonus_token.
+ * Errors: INVALID_ARG, INVALID_TREE, TOKEN_RANGE, KV_CAPACITY, STATE (no pending
+ * token), DEVICE. */
+ts_status ts_verify(ts_model* m, ts_kv* kv,
+                    const int32_t* draft_tokens, const int32_t* parent_idx, int32_t n_nodes,
+                    int32_t* accept_len, int32_t* accepted_tokens, int32_t* accepted_nodes,
+                    int32_t* bonus_token);
+
+/* Same for n_seqs independent sequences in one pass (weights are streamed once).
+ * Nodes are concatenated; node_offsets has n_seqs + 1 entries; parent indices are
+ * local to their sequence.  accepted_tokens / accepted_nodes use the same offsets.
+ * All kvs must belong to m and be distinct. */
+ts_status ts_verify_batch(ts_model* m, ts_kv* const* kvs, int32_t n_seqs,
+                          const int32_t* draft_tokens, const int32_t* parent_idx,
+                          const int32_t* node_offsets,
+                          int32_t* accept_len, int32_t* accepted_tokens, int32_t* accepted_nodes,
+                          int32_t* bonus_token);
+
+/* ---- commit (Alg. 1: y <- y (+) accepted prefix) ------------------------------
+ * Applies the most recent verify on this cache: the root's K/V stay at slot len,
+ * the accepted node of depth d moves to slot len + d (all layers, all KV heads,
+ * a pure copy since K is stored rotated), len += l + 1, pending <- bonus token.
+ * STATE if there is no unapplied verify result. */
+ts_status ts_kv_commit(ts_kv* kv);
+
+/* ---- measurement --------------------------------------------------------------
+ * With profiling on, every kernel launch of ts_verify is bracketed by HIP events on
+ * the model's stream.  ts_profile_read returns, for up to max_entries kernel kinds
+ * launched by the most recent verify: name (static string), launches, total ms.
+ * It returns the number of kinds through n_entries. */
+typedef struct { const char* name; int32_t launches; float total_ms; } ts_profile_entry;
+ts_status ts_profile_enable(ts_model* m, int32_t enable);
+ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_entries, int32_t* n_entries);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOOLSPEC_H */

@@ -1,0 +1,749 @@
+// Host side of libtoolspec_hip.so: the C ABI of include/toolspec.h, model / cache
+// ownership, argument validation, and the launch sequence of one verify pass.
+// All arithmetic of the pass runs in the kernels; the host only validates the tree,
+// derives per-row bookkeeping (depth, position, ancestor bit set) and orders launches.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <map>
+#include <new>
+
+#include "ts_internal.h"
+
+// ---------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------
+static thread_local std::string g_last_error;
+
+ts_status ts_fail(ts_status code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+extern "C" const char* ts_last_error(void) { return g_last_error.c_str(); }
+
+// ---------------------------------------------------------------------------------
+// profiling brackets
+// ---------------------------------------------------------------------------------
+void prof_begin(ts_model* m, const char* name) {
+  while (m->ev_pool.size() < m->ev_used + 2) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    m->ev_pool.push_back(e);
+  }
+  ProfRec r;
+  r.name = name;
+  r.a = m->ev_pool[m->ev_used++];
+  r.b = m->ev_pool[m->ev_used++];
+  hipEventRecord(r.a, m->stream);
+  m->prof.push_back(r);
+}
+void prof_end(ts_model* m) {
+  if (!m->prof.empty()) hipEventRecord(m->prof.back().b, m->stream);
+}
+
+// ---------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------
+static inline float bf16_bits_to_float(uint16_t u) {
+  uint32_t b = (uint32_t)u << 16;
+  float f;
+  memcpy(&f, &b, 4);
+  return f;
+}
+
+template <typename T>
+static ts_status dev_alloc(T** p, size_t count) {
+  void* q = nullptr;
+  hipError_t e = hipMalloc(&q, std::max<size_t>(count * sizeof(T), 256));
+  if (e != hipSuccess) return ts_fail(TS_ERR_OOM, "hipMalloc of %zu bytes failed: %s", count * sizeof(T), hipGetErrorString(e));
+  *p = (T*)q;
+  return TS_OK;
+}
+static ts_status dev_alloc_bytes(void** p, size_t bytes, bool zero) {
+  hipError_t e = hipMalloc(p, std::max<size_t>(bytes, 256));
+  if (e != hipSuccess) return ts_fail(TS_ERR_OOM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+  if (zero) {
+    e = hipMemset(*p, 0, std::max<size_t>(bytes, 256));
+    if (e == hipSuccess) e = hipDeviceSynchronize();   // allocations are rare; later work runs on a non-blocking stream
+    if (e != hipSuccess) return ts_fail(TS_ERR_DEVICE, "hipMemset failed: %s", hipGetErrorString(e));
+  }
+  return TS_OK;
+}
+static void dev_free(void* p) { if (p) (void)hipFree(p); }
+
+// Stream-ordered copy followed by a wait: the model's stream is non-blocking, so copies on
+// the null stream would not be ordered against its kernels.
+static hipError_t copy_sync(hipStream_t s, void* dst, const void* src, size_t bytes, hipMemcpyKind kind) {
+  hipError_t e = hipMemcpyAsync(dst, src, bytes, kind, s);
+  if (e != hipSuccess) return e;
+  return hipStreamSynchronize(s);
+}
+
+static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// ---------------------------------------------------------------------------------
+// model
+// ---------------------------------------------------------------------------------
+static ts_status check_config(const ts_model_config& c) {
+  if (c.n_layers < 1 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.head_dim < 1 || c.d_ffn < 1 || c.vocab < 1)
+    return ts_fail(TS_ERR_INVALID_ARG, "model config: all sizes must be positive");
+  if (c.n_q_heads % c.n_kv_heads) return ts_fail(TS_ERR_INVALID_ARG, "n_q_heads must be a multiple of n_kv_heads");
+  if (!(c.rms_eps > 0.f) || !(c.rope_theta > 0.f)) return ts_fail(TS_ERR_INVALID_ARG, "rms_eps and rope_theta must be positive");
+  if (c.d_ffn % 16) return ts_fail(TS_ERR_INVALID_ARG, "d_ffn must be a multiple of 16");
+  if (c.dtype == TS_DTYPE_BF16) {
+    if (c.d_model % 128 || (c.n_q_heads * c.head_dim) % 128 || c.d_ffn % 128)
+      return ts_fail(TS_ERR_INVALID_ARG, "bf16 path: d_model, n_q_heads*head_dim and d_ffn must be multiples of 128");
+    if (c.head_dim != 64 && c.head_dim != 128) return ts_fail(TS_ERR_INVALID_ARG, "bf16 path: head_dim must be 64 or 128");
+    if (!is_pow2(c.n_q_heads / c.n_kv_heads)) return ts_fail(TS_ERR_INVALID_ARG, "bf16 path: query heads per KV head must be a power of two");
+  } else if (c.dtype == TS_DTYPE_F32) {
+    if (!is_pow2(c.head_dim) || c.head_dim < 2 || c.head_dim > 128)
+      return ts_fail(TS_ERR_INVALID_ARG, "fp32 path: head_dim must be a power of two in [2,128]");
+  } else {
+    return ts_fail(TS_ERR_INVALID_ARG, "dtype must be TS_DTYPE_F32 or TS_DTYPE_BF16");
+  }
+  return TS_OK;
+}
+
+static void free_workspace(ts_model* m) {
+  dev_free(m->H); dev_free(m->Xn); dev_free(m->Qb); dev_free(m->Ab); dev_free(m->Fb); dev_free(m->part);
+  dev_free(m->attn_part_o); dev_free(m->attn_part_ml); dev_free(m->rope_cs); dev_free(m->amax_val);
+  dev_free(m->amax_idx); dev_free(m->logits); dev_free(m->meta_dev); dev_free(m->seq_dev);
+  if (m->meta_host) (void)hipHostFree(m->meta_host);
+  if (m->res_host) (void)hipHostFree(m->res_host);
+  m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr;
+  m->attn_part_o = m->attn_part_ml = nullptr; m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr;
+  m->logits = nullptr; m->meta_dev = nullptr; m->seq_dev = nullptr; m->meta_host = nullptr; m->res_host = nullptr;
+  m->ws_rows = 0; m->ws_seqs = 0; m->logits_rows = 0; m->attn_max_splits = 0;
+}
+
+static size_t meta_bytes_for(int rows) { return (size_t)rows * (6 * sizeof(int32_t) + sizeof(uint64_t)); }
+
+// Row buffers carry TS_MROWS_PER_BLOCK spare rows: tile-granular kernels read (never use)
+// rows past the last real one.
+static ts_status ensure_workspace(ts_model* m, int rows, int seqs) {
+  const ts_model_config& c = m->cfg;
+  ts_status st;
+  if (rows > m->ws_rows || seqs > m->ws_seqs) {
+    TS_HIP(hipStreamSynchronize(m->stream));
+    const bool keep = m->keep_logits;
+    free_workspace(m);
+    const int cap = ((rows + TS_MROWS_PER_BLOCK - 1) / TS_MROWS_PER_BLOCK) * TS_MROWS_PER_BLOCK;
+    const int alloc_rows = cap + TS_MROWS_PER_BLOCK;
+    const int scap = std::max(seqs, 1);
+    const size_t esz = m->esz;
+    if ((st = dev_alloc_bytes((void**)&m->H, (size_t)alloc_rows * c.d_model * 4, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Xn, (size_t)alloc_rows * c.d_model * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Qb, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Ab, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Fb, (size_t)alloc_rows * c.d_ffn * esz, true))) return st;
+    size_t pe = 0;
+    if (c.dtype == TS_DTYPE_BF16) {
+      const int Ns[4] = {m->qkv_dim, c.d_model, 2 * c.d_ffn, c.d_model};
+      const int Ks[4] = {c.d_model, m->q_dim, c.d_model, c.d_ffn};
+      for (int i = 0; i < 4; ++i) pe = std::max(pe, (size_t)gemm_bf16_plan(m, Ns[i], Ks[i]).splits * cap * Ns[i]);
+    } else {
+      pe = (size_t)cap * std::max(std::max(m->qkv_dim, 2 * c.d_ffn), c.d_model);
+    }
+    m->part_elems = pe;
+    if ((st = dev_alloc_bytes((void**)&m->part, pe * 4, true))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->rope_cs, (size_t)alloc_rows * (c.head_dim / 2) * sizeof(float2), true))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->amax_val, (size_t)alloc_rows * m->amax_parts * 4, true))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->amax_idx, (size_t)alloc_rows * m->amax_parts * 4, true))) return st;
+    m->meta_bytes = meta_bytes_for(alloc_rows);
+    if ((st = dev_alloc_bytes(&m->meta_dev, m->meta_bytes, true))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->seq_dev, (size_t)scap * sizeof(SeqDesc), true))) return st;
+    TS_HIP(hipHostMalloc(&m->meta_host, m->meta_bytes + (size_t)scap * sizeof(SeqDesc), hipHostMallocDefault));
+    TS_HIP(hipHostMalloc((void**)&m->res_host, (size_t)scap * TS_RESULT_INTS * sizeof(int32_t), hipHostMallocDefault));
+    m->ws_rows = cap;
+    m->ws_seqs = scap;
+    m->keep_logits = keep;
+  }
+  const bool need_logits = m->keep_logits || c.dtype == TS_DTYPE_F32;
+  if (need_logits && m->logits_rows < m->ws_rows) {
+    TS_HIP(hipStreamSynchronize(m->stream));
+    dev_free(m->logits);
+    m->logits = nullptr;
+    if ((st = dev_alloc_bytes((void**)&m->logits, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * c.vocab * 4, true))) return st;
+    m->logits_rows = m->ws_rows;
+  }
+  return TS_OK;
+}
+
+static ts_status ensure_attn_partials(ts_model* m, int splits, int R) {
+  if (m->cfg.dtype != TS_DTYPE_BF16) return TS_OK;
+  const size_t need = (size_t)splits * R;
+  if (need <= (size_t)m->attn_max_splits) return TS_OK;   // attn_max_splits counts split*row slots
+  TS_HIP(hipStreamSynchronize(m->stream));
+  dev_free(m->attn_part_o); dev_free(m->attn_part_ml);
+  m->attn_part_o = m->attn_part_ml = nullptr;
+  m->attn_max_splits = 0;
+  ts_status st;
+  if ((st = dev_alloc_bytes((void**)&m->attn_part_o, need * m->q_dim * 4, true))) return st;
+  if ((st = dev_alloc_bytes((void**)&m->attn_part_ml, need * m->cfg.n_q_heads * 2 * 4, true))) return st;
+  m->attn_max_splits = (int)need;
+  return TS_OK;
+}
+
+// Upload one host matrix [N][K] and leave it on the device in the layout its GEMM reads.
+// bf16: staged row-major, then re-tiled into dst at tile offset n_tile0 (stride n_tile_stride).
+// f32 : copied row-major to dst + row_off rows.
+static ts_status upload_matrix(ts_model* m, const void* host, int N, int K, void* dst, void* staging, int n_tile0,
+                               int n_tile_stride, int f32_row_off) {
+  if (!host) return ts_fail(TS_ERR_INVALID_ARG, "null weight pointer");
+  if (m->cfg.dtype == TS_DTYPE_BF16) {
+    TS_HIP(copy_sync(m->stream, staging, host, (size_t)N * K * 2, hipMemcpyHostToDevice));
+    launch_repack_tiles(m->stream, (const bf16_t*)staging, (bf16_t*)dst, N, K, n_tile0, n_tile_stride);
+    TS_HIP(hipGetLastError());
+    TS_HIP(hipStreamSynchronize(m->stream));
+  } else {
+    TS_HIP(copy_sync(m->stream, (float*)dst + (size_t)f32_row_off * K, host, (size_t)N * K * 4, hipMemcpyHostToDevice));
+  }
+  return TS_OK;
+}
+
+static ts_status upload_gain(ts_model* m, const void* host, float** dst) {
+  if (!host) return ts_fail(TS_ERR_INVALID_ARG, "null norm pointer");
+  const int d = m->cfg.d_model;
+  std::vector<float> tmp(d);
+  if (m->cfg.dtype == TS_DTYPE_BF16)
+    for (int i = 0; i < d; ++i) tmp[i] = bf16_bits_to_float(((const uint16_t*)host)[i]);
+  else
+    memcpy(tmp.data(), host, (size_t)d * 4);
+  ts_status st = dev_alloc(dst, (size_t)d);
+  if (st) return st;
+  TS_HIP(copy_sync(m->stream, *dst, tmp.data(), (size_t)d * 4, hipMemcpyHostToDevice));
+  return TS_OK;
+}
+
+static size_t tiled_elems(int N, int K) { return (size_t)((N + 15) / 16) * 16 * K; }
+
+static ts_status model_load_impl(ts_model* m, const ts_weights* w) {
+  const ts_model_config& c = m->cfg;
+  ts_status st;
+  const bool bf = c.dtype == TS_DTYPE_BF16;
+  const size_t esz = m->esz;
+  const int d = c.d_model, F = c.d_ffn, V = c.vocab;
+  if (!w->embed || !w->lm_head || !w->norm_f || !w->wq || !w->wk || !w->wv || !w->wo || !w->wg || !w->wu || !w->wd ||
+      !w->norm1 || !w->norm2)
+    return ts_fail(TS_ERR_INVALID_ARG, "ts_weights has a null member");
+
+  void* staging = nullptr;
+  if (bf) {
+    size_t big = std::max((size_t)V * d, (size_t)F * d);
+    big = std::max(big, (size_t)m->q_dim * d);
+    if ((st = dev_alloc_bytes(&staging, big * 2, false))) return st;
+  }
+  auto matrix_bytes = [&](int N, int K) { return (bf ? tiled_elems(N, K) : (size_t)N * K) * esz; };
+
+  // embedding stays row-major in the storage dtype (it is gathered, not multiplied)
+  if ((st = dev_alloc_bytes(&m->embed, (size_t)V * d * esz, false))) { dev_free(staging); return st; }
+  {
+    hipError_t e = copy_sync(m->stream, m->embed, w->embed, (size_t)V * d * esz, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { dev_free(staging); return ts_fail(TS_ERR_DEVICE, "embedding upload failed: %s", hipGetErrorString(e)); }
+  }
+  st = dev_alloc_bytes(&m->lm_head, matrix_bytes(V, d), false);
+  if (!st) st = upload_matrix(m, w->lm_head, V, d, m->lm_head, staging, 0, 1, 0);
+  if (!st) st = upload_gain(m, w->norm_f, &m->norm_f);
+
+  m->layers.assign(c.n_layers, LayerW{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr});
+  std::vector<float> gu_host;
+  for (int l = 0; l < c.n_layers && !st; ++l) {
+    LayerW& L = m->layers[l];
+    if (!w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->wg[l] || !w->wu[l] || !w->wd[l] || !w->norm1[l] || !w->norm2[l]) {
+      st = ts_fail(TS_ERR_INVALID_ARG, "null weight pointer in layer %d", l);
+      break;
+    }
+    if ((st = dev_alloc_bytes(&L.wqkv, matrix_bytes(m->qkv_dim, d), false))) break;
+    if ((st = dev_alloc_bytes(&L.wo, matrix_bytes(d, m->q_dim), false))) break;
+    if ((st = dev_alloc_bytes(&L.wgu, matrix_bytes(2 * F, d), false))) break;
+    if ((st = dev_alloc_bytes(&L.wd, matrix_bytes(d, F), false))) break;
+    // fused QKV: rows [q | k | v]
+    if ((st = upload_matrix(m, w->wq[l], m->q_dim, d, L.wqkv, staging, 0, 1, 0))) break;
+    if ((st = upload_matrix(m, w->wk[l], m->kv_dim, d, L.wqkv, staging, m->q_dim / 16, 1, m->q_dim))) break;
+    if ((st = upload_matrix(m, w->wv[l], m->kv_dim, d, L.wqkv, staging, (m->q_dim + m->kv_dim) / 16, 1, m->q_dim + m->kv_dim))) break;
+    if ((st = upload_matrix(m, w->wo[l], d, m->q_dim, L.wo, staging, 0, 1, 0))) break;
+    // fused gate/up: 16-row tiles alternate gate, up, gate, up, ...
+    if (bf) {
+      if ((st = upload_matrix(m, w->wg[l], F, d, L.wgu, staging, 0, 2, 0))) break;
+      if ((st = upload_matrix(m, w->wu[l], F, d, L.wgu, staging, 1, 2, 0))) break;
+    } else {
+      gu_host.resize((size_t)2 * F * d);
+      const float* g = (const float*)w->wg[l];
+      const float* u = (const float*)w->wu[l];
+      for (int t = 0; t < F / 16; ++t) {
+        memcpy(&gu_host[(size_t)(2 * t) * 16 * d], g + (size_t)t * 16 * d, (size_t)16 * d * 4);
+        memcpy(&gu_host[(size_t)(2 * t + 1) * 16 * d], u + (size_t)t * 16 * d, (size_t)16 * d * 4);
+      }
+      if ((st = upload_matrix(m, gu_host.data(), 2 * F, d, L.wgu, staging, 0, 1, 0))) break;
+    }
+    if ((st = upload_matrix(m, w->wd[l], d, F, L.wd, staging, 0, 1, 0))) break;
+    if ((st = upload_gain(m, w->norm1[l], &L.norm1))) break;
+    if ((st = upload_gain(m, w->norm2[l], &L.norm2))) break;
+  }
+  dev_free(staging);
+  return st;
+}
+
+extern "C" ts_status ts_model_free(ts_model* m) {
+  if (!m) return TS_OK;
+  (void)hipSetDevice(m->device);
+  if (m->stream) (void)hipStreamSynchronize(m->stream);
+  free_workspace(m);
+  dev_free(m->embed); dev_free(m->lm_head); dev_free(m->norm_f);
+  for (LayerW& L : m->layers) {
+    dev_free(L.wqkv); dev_free(L.wo); dev_free(L.wgu); dev_free(L.wd); dev_free(L.norm1); dev_free(L.norm2);
+  }
+  for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
+  if (m->stream) (void)hipStreamDestroy(m->stream);
+  delete m;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights* w, ts_model** out) {
+  if (!cfg || !w || !out) return ts_fail(TS_ERR_INVALID_ARG, "ts_model_load: null argument");
+  *out = nullptr;
+  ts_status st = check_config(*cfg);
+  if (st) return st;
+  ts_model* m = new (std::nothrow) ts_model();
+  if (!m) return ts_fail(TS_ERR_OOM, "host allocation failed");
+  m->cfg = *cfg;
+  m->esz = cfg->dtype == TS_DTYPE_BF16 ? 2 : 4;
+  m->q_dim = cfg->n_q_heads * cfg->head_dim;
+  m->kv_dim = cfg->n_kv_heads * cfg->head_dim;
+  m->qkv_dim = m->q_dim + 2 * m->kv_dim;
+  m->stream = nullptr;
+  m->embed = m->lm_head = nullptr; m->norm_f = nullptr;
+  m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr; m->part_elems = 0;
+  m->attn_part_o = m->attn_part_ml = nullptr; m->attn_max_splits = 0;
+  m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr; m->logits = nullptr;
+  m->keep_logits = false; m->logits_rows = 0; m->meta_dev = nullptr; m->meta_host = nullptr; m->meta_bytes = 0;
+  m->seq_dev = nullptr; m->res_host = nullptr; m->ws_rows = 0; m->ws_seqs = 0;
+  m->prof_on = false; m->ev_used = 0; m->last_rows = 0;
+  hipError_t e = hipGetDevice(&m->device);
+  hipDeviceProp_t prop;
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, m->device);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&m->stream, hipStreamNonBlocking);
+  if (e != hipSuccess) {
+    delete m;
+    return ts_fail(TS_ERR_DEVICE, "device setup failed: %s", hipGetErrorString(e));
+  }
+  m->n_cu = prop.multiProcessorCount;
+  if (cfg->dtype == TS_DTYPE_BF16) {
+    const GemmPlan p = gemm_bf16_plan(m, cfg->vocab, cfg->d_model);
+    const int n_tiles = (cfg->vocab + 15) / 16;
+    m->amax_parts = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
+  } else {
+    m->amax_parts = 1;
+  }
+  st = model_load_impl(m, w);
+  if (!st) st = ensure_workspace(m, TS_MAX_NODES + 1, 1);
+  if (st) {
+    std::string keep = g_last_error;
+    ts_model_free(m);
+    g_last_error = keep;
+    return st;
+  }
+  *out = m;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_model_keep_logits(ts_model* m, int32_t enable) {
+  if (!m) return ts_fail(TS_ERR_INVALID_ARG, "null model");
+  (void)hipSetDevice(m->device);
+  m->keep_logits = enable != 0;
+  return ensure_workspace(m, m->ws_rows, m->ws_seqs);
+}
+
+extern "C" ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, float* host) {
+  if (!m || !host) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  if (!m->logits || !(m->keep_logits || m->cfg.dtype == TS_DTYPE_F32) || m->last_rows == 0)
+    return ts_fail(TS_ERR_STATE, "no logits kept: call ts_model_keep_logits(m, 1) before ts_verify");
+  if (row0 < 0 || n_rows < 0 || row0 + n_rows > m->last_rows)
+    return ts_fail(TS_ERR_INVALID_ARG, "rows [%d,%d) outside the last pass (%d rows)", row0, row0 + n_rows, m->last_rows);
+  (void)hipSetDevice(m->device);
+  TS_HIP(hipStreamSynchronize(m->stream));
+  TS_HIP(copy_sync(m->stream, host, m->logits + (size_t)row0 * m->cfg.vocab, (size_t)n_rows * m->cfg.vocab * 4, hipMemcpyDeviceToHost));
+  return TS_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// KV cache
+// ---------------------------------------------------------------------------------
+extern "C" ts_status ts_kv_free(ts_kv* kv) {
+  if (!kv) return TS_OK;
+  (void)hipSetDevice(kv->model->device);
+  (void)hipStreamSynchronize(kv->model->stream);
+  dev_free(kv->k_pool); dev_free(kv->v_pool); dev_free(kv->page_table); dev_free(kv->result);
+  delete kv;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_alloc(ts_model* m, int32_t capacity, int32_t page_size, ts_kv** out) {
+  if (!m || !out) return ts_fail(TS_ERR_INVALID_ARG, "ts_kv_alloc: null argument");
+  *out = nullptr;
+  if (page_size != TS_PAGE_SIZE) return ts_fail(TS_ERR_INVALID_ARG, "page_size must be %d", TS_PAGE_SIZE);
+  if (capacity < 1) return ts_fail(TS_ERR_INVALID_ARG, "capacity_tokens must be positive");
+  (void)hipSetDevice(m->device);
+  ts_kv* kv = new (std::nothrow) ts_kv();
+  if (!kv) return ts_fail(TS_ERR_OOM, "host allocation failed");
+  const ts_model_config& c = m->cfg;
+  kv->model = m;
+  kv->capacity = capacity;
+  kv->page_size = page_size;
+  kv->n_pages = (capacity + page_size - 1) / page_size;
+  kv->P = 0;
+  kv->pending = -1;
+  kv->have_result = false;
+  kv->last_M = 0;
+  kv->k_pool = kv->v_pool = nullptr; kv->page_table = nullptr; kv->result = nullptr;
+  kv->layer_stride_elems = (size_t)kv->n_pages * c.n_kv_heads * 16 * c.head_dim;
+  const size_t bytes = kv->layer_stride_elems * c.n_layers * m->esz;
+  ts_status st = dev_alloc_bytes(&kv->k_pool, bytes, true);
+  if (!st) st = dev_alloc_bytes(&kv->v_pool, bytes, true);
+  if (!st) st = dev_alloc_bytes((void**)&kv->page_table, (size_t)kv->n_pages * 4, false);
+  if (!st) st = dev_alloc_bytes((void**)&kv->result, TS_RESULT_INTS * 4, true);
+  if (!st) {
+    kv->page_table_host.resize(kv->n_pages);
+    for (int i = 0; i < kv->n_pages; ++i) kv->page_table_host[i] = i;
+    hipError_t e = copy_sync(m->stream, kv->page_table, kv->page_table_host.data(), (size_t)kv->n_pages * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) st = ts_fail(TS_ERR_DEVICE, "page table upload failed: %s", hipGetErrorString(e));
+  }
+  if (st) {
+    std::string keep = g_last_error;
+    ts_kv_free(kv);
+    g_last_error = keep;
+    return st;
+  }
+  *out = kv;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_set_page_table(ts_kv* kv, const int32_t* phys, int32_t n_pages) {
+  if (!kv || !phys) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  if (kv->P != 0) return ts_fail(TS_ERR_STATE, "page table can only change while the cache is empty");
+  if (n_pages != kv->n_pages) return ts_fail(TS_ERR_INVALID_ARG, "n_pages must be %d", kv->n_pages);
+  std::vector<char> seen(n_pages, 0);
+  for (int i = 0; i < n_pages; ++i) {
+    if (phys[i] < 0 || phys[i] >= n_pages || seen[phys[i]]) return ts_fail(TS_ERR_INVALID_ARG, "page table is not a permutation");
+    seen[phys[i]] = 1;
+  }
+  (void)hipSetDevice(kv->model->device);
+  TS_HIP(hipStreamSynchronize(kv->model->stream));
+  kv->page_table_host.assign(phys, phys + n_pages);
+  TS_HIP(copy_sync(kv->model->stream, kv->page_table, phys, (size_t)n_pages * 4, hipMemcpyHostToDevice));
+  return TS_OK;
+}
+
+static ts_status kv_xfer_impl(ts_kv* kv, int pos0, int n_pos, const void* k_in, const void* v_in, void* k_out, void* v_out) {
+  ts_model* m = kv->model;
+  const ts_model_config& c = m->cfg;
+  if (n_pos == 0) return TS_OK;
+  (void)hipSetDevice(m->device);
+  const size_t slab = (size_t)n_pos * c.n_kv_heads * c.head_dim * m->esz;   // one layer
+  void *sk = nullptr, *sv = nullptr;
+  ts_status st = dev_alloc_bytes(&sk, slab, false);
+  if (!st) st = dev_alloc_bytes(&sv, slab, false);
+  hipError_t e = hipSuccess;
+  for (int l = 0; l < c.n_layers && !st && e == hipSuccess; ++l) {
+    if (k_in) {
+      e = copy_sync(m->stream, sk, (const char*)k_in + (size_t)l * slab, slab, hipMemcpyHostToDevice);
+      if (e == hipSuccess) e = copy_sync(m->stream, sv, (const char*)v_in + (size_t)l * slab, slab, hipMemcpyHostToDevice);
+      if (e == hipSuccess) { launch_kv_import(kv, pos0, n_pos, sk, sv, l); e = hipGetLastError(); }
+      if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    } else {
+      launch_kv_export(kv, pos0, n_pos, sk, sv, l);
+      e = hipGetLastError();
+      if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+      if (e == hipSuccess) e = copy_sync(m->stream, (char*)k_out + (size_t)l * slab, sk, slab, hipMemcpyDeviceToHost);
+      if (e == hipSuccess) e = copy_sync(m->stream, (char*)v_out + (size_t)l * slab, sv, slab, hipMemcpyDeviceToHost);
+    }
+  }
+  dev_free(sk); dev_free(sv);
+  if (st) return st;
+  if (e != hipSuccess) return ts_fail(TS_ERR_DEVICE, "KV transfer failed: %s", hipGetErrorString(e));
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_import(ts_kv* kv, int32_t n_pos, const void* k_host, const void* v_host) {
+  if (!kv || (n_pos > 0 && (!k_host || !v_host))) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  if (n_pos < 0 || n_pos > kv->capacity) return ts_fail(TS_ERR_KV_CAPACITY, "n_pos %d outside [0, capacity %d]", n_pos, kv->capacity);
+  ts_status st = kv_xfer_impl(kv, 0, n_pos, k_host, v_host, nullptr, nullptr);
+  if (st) return st;
+  kv->P = n_pos;
+  kv->have_result = false;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_export(ts_kv* kv, int32_t pos0, int32_t n_pos, void* k_host, void* v_host) {
+  if (!kv || (n_pos > 0 && (!k_host || !v_host))) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  if (pos0 < 0 || n_pos < 0 || pos0 + n_pos > kv->capacity)
+    return ts_fail(TS_ERR_INVALID_ARG, "positions [%d,%d) outside the capacity %d", pos0, pos0 + n_pos, kv->capacity);
+  return kv_xfer_impl(kv, pos0, n_pos, nullptr, nullptr, k_host, v_host);
+}
+
+extern "C" ts_status ts_set_pending(ts_kv* kv, int32_t token) {
+  if (!kv) return ts_fail(TS_ERR_INVALID_ARG, "null cache");
+  if (token < 0 || token >= kv->model->cfg.vocab) return ts_fail(TS_ERR_TOKEN_RANGE, "token %d outside [0,%d)", token, kv->model->cfg.vocab);
+  kv->pending = token;
+  kv->have_result = false;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_len(const ts_kv* kv, int32_t* len) {
+  if (!kv || !len) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  *len = kv->P;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_truncate(ts_kv* kv, int32_t new_len) {
+  if (!kv) return ts_fail(TS_ERR_INVALID_ARG, "null cache");
+  if (new_len < 0 || new_len > kv->P) return ts_fail(TS_ERR_INVALID_ARG, "new_len %d outside [0,%d]", new_len, kv->P);
+  kv->P = new_len;
+  kv->have_result = false;
+  return TS_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// verify
+// ---------------------------------------------------------------------------------
+static RowMeta carve_meta(void* base, int rows) {
+  RowMeta rm;
+  char* p = (char*)base;
+  rm.anc = (uint64_t*)p; p += (size_t)rows * sizeof(uint64_t);
+  rm.tok = (int32_t*)p;  p += (size_t)rows * 4;
+  rm.pos = (int32_t*)p;  p += (size_t)rows * 4;
+  rm.seq = (int32_t*)p;  p += (size_t)rows * 4;
+  rm.lrow = (int32_t*)p; p += (size_t)rows * 4;
+  rm.par = (int32_t*)p;  p += (size_t)rows * 4;
+  rm.depth = (int32_t*)p;
+  return rm;
+}
+
+static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const int32_t* toks, const int32_t* pars,
+                             const int32_t* offs, int32_t* accept_len, int32_t* acc_tokens, int32_t* acc_nodes,
+                             int32_t* bonus) {
+  const ts_model_config& c = m->cfg;
+  const bool bf = c.dtype == TS_DTYPE_BF16;
+  // ---- validation (nothing is modified before it passes) ---------------------------
+  int R = 0, max_M = 0, max_keys = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    ts_kv* kv = kvs[s];
+    if (!kv) return ts_fail(TS_ERR_INVALID_ARG, "null cache handle (sequence %d)", s);
+    if (kv->model != m) return ts_fail(TS_ERR_INVALID_ARG, "cache %d belongs to another model", s);
+    for (int t = 0; t < s; ++t)
+      if (kvs[t] == kv) return ts_fail(TS_ERR_INVALID_ARG, "cache handle used twice in one batch");
+    const int n = offs[s + 1] - offs[s];
+    if (n < 0 || n > TS_MAX_NODES) return ts_fail(TS_ERR_INVALID_TREE, "n_nodes %d outside [0,%d] (sequence %d)", n, TS_MAX_NODES, s);
+    if (n > 0 && (!toks || !pars)) return ts_fail(TS_ERR_INVALID_ARG, "null draft arrays with n_nodes > 0");
+    if (kv->pending < 0) return ts_fail(TS_ERR_STATE, "no pending token (sequence %d): call ts_set_pending or commit a verify", s);
+    if (kv->P + n + 1 > kv->capacity)
+      return ts_fail(TS_ERR_KV_CAPACITY, "committed %d + tree rows %d exceed the capacity %d (sequence %d)", kv->P, n + 1, kv->capacity, s);
+    for (int i = 0; i < n; ++i) {
+      const int p = pars[offs[s] + i], t = toks[offs[s] + i];
+      if (p < -1 || p >= i) return ts_fail(TS_ERR_INVALID_TREE, "parent_idx[%d] = %d outside [-1,%d) (sequence %d)", i, p, i, s);
+      if (t < 0 || t >= c.vocab) return ts_fail(TS_ERR_TOKEN_RANGE, "draft token %d outside [0,%d) (node %d, sequence %d)", t, c.vocab, i, s);
+    }
+    R += n + 1;
+    max_M = std::max(max_M, n + 1);
+    max_keys = std::max(max_keys, kv->P + n + 1);
+  }
+  if (!bf && (size_t)max_keys > attn_f32_max_keys())
+    return ts_fail(TS_ERR_KV_CAPACITY, "fp32 path supports at most %zu keys per sequence", attn_f32_max_keys());
+
+  (void)hipSetDevice(m->device);
+  ts_status st = ensure_workspace(m, R, n_seqs);
+  if (st) return st;
+  const int splits = bf ? attn_bf16_splits(m, max_keys, n_seqs) : 1;
+  if ((st = ensure_attn_partials(m, splits, R))) return st;
+
+  // ---- per-row bookkeeping (Alg. 1: flattened sequence + tree mask) ------------------
+  const int alloc_rows = m->ws_rows + TS_MROWS_PER_BLOCK;
+  RowMeta hm = carve_meta(m->meta_host, alloc_rows);
+  RowMeta dm = carve_meta(m->meta_dev, alloc_rows);
+  SeqDesc* hseq = (SeqDesc*)((char*)m->meta_host + m->meta_bytes);
+  int r0 = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    ts_kv* kv = kvs[s];
+    const int n = offs[s + 1] - offs[s];
+    hm.tok[r0] = kv->pending; hm.pos[r0] = kv->P; hm.seq[r0] = s; hm.lrow[r0] = 0;
+    hm.par[r0] = -1; hm.depth[r0] = 0; hm.anc[r0] = 0;
+    for (int i = 0; i < n; ++i) {
+      const int r = r0 + i + 1;
+      const int prow = pars[offs[s] + i] + 1;             // local parent row
+      hm.tok[r] = toks[offs[s] + i];
+      hm.seq[r] = s; hm.lrow[r] = i + 1; hm.par[r] = prow;
+      hm.depth[r] = hm.depth[r0 + prow] + 1;
+      hm.pos[r] = kv->P + hm.depth[r];
+      hm.anc[r] = hm.anc[r0 + prow] | (1ull << i);
+    }
+    SeqDesc& sd = hseq[s];
+    sd.P = kv->P; sd.M = n + 1; sd.row0 = r0; sd.n_pages = kv->n_pages;
+    sd.page_table = kv->page_table; sd.k_pool = kv->k_pool; sd.v_pool = kv->v_pool; sd.result = kv->result;
+    kv->have_result = false;
+    r0 += n + 1;
+  }
+  TS_HIP(hipMemcpyAsync(m->meta_dev, m->meta_host, m->meta_bytes, hipMemcpyHostToDevice, m->stream));
+  TS_HIP(hipMemcpyAsync(m->seq_dev, hseq, (size_t)n_seqs * sizeof(SeqDesc), hipMemcpyHostToDevice, m->stream));
+
+  // ---- the pass ---------------------------------------------------------------------
+  m->prof.clear();
+  m->ev_used = 0;
+  const int d = c.d_model, F = c.d_ffn;
+  launch_embed(m, dm, R);
+  launch_rope_table(m, dm, R);
+  int pending_parts = 0;          // split-K partials of the previous projection still to be added to H
+  size_t pending_stride = 0;
+  auto project = [&](const char* name, const void* X, const void* W, int N, int K, int* n_parts, size_t* stride) {
+    if (bf) {
+      const GemmPlan p = gemm_bf16_plan(m, N, K);
+      ProfScope ps(m, name);
+      launch_gemm_bf16(m, (const bf16_t*)X, (const bf16_t*)W, m->part, R, N, K, p, false, nullptr);
+      *n_parts = p.splits;
+      *stride = (size_t)R * N;
+    } else {
+      launch_gemm_f32(m, (const float*)X, (const float*)W, m->part, R, N, K);
+      *n_parts = 1;
+      *stride = (size_t)R * N;
+    }
+  };
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW& L = m->layers[l];
+    int np; size_t ps;
+    launch_norm(m, R, L.norm1, pending_parts, pending_stride, l == 0);
+    project("gemm_qkv", m->Xn, L.wqkv, m->qkv_dim, d, &np, &ps);
+    launch_rope_kv(m, dm, R, l, np, ps);
+    if (bf) {
+      launch_attn_bf16(m, dm, R, n_seqs, l, splits, max_M);
+      launch_attn_merge(m, R, splits);
+    } else {
+      launch_attn_f32(m, dm, R, n_seqs, l, max_keys);
+    }
+    project("gemm_o", m->Ab, L.wo, d, m->q_dim, &np, &ps);
+    launch_norm(m, R, L.norm2, np, ps, false);
+    project("gemm_gate_up", m->Xn, L.wgu, 2 * F, d, &np, &ps);
+    launch_swiglu(m, R, np, ps);
+    project("gemm_down", m->Fb, L.wd, d, F, &pending_parts, &pending_stride);
+  }
+  launch_norm(m, R, m->norm_f, pending_parts, pending_stride, false);
+  if (bf) {
+    const GemmPlan p = gemm_bf16_plan(m, c.vocab, d);
+    ProfScope ps(m, "gemm_lm_head_argmax");
+    launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)m->lm_head, nullptr, R, c.vocab, d, p, true,
+                     m->keep_logits ? m->logits : nullptr);
+  } else {
+    launch_gemm_f32(m, (const float*)m->Xn, (const float*)m->lm_head, m->logits, R, c.vocab, d);
+    launch_argmax_rows(m, R);
+  }
+  launch_walk(m, dm, n_seqs);
+  TS_HIP(hipGetLastError());
+  for (int s = 0; s < n_seqs; ++s)
+    TS_HIP(hipMemcpyAsync(m->res_host + (size_t)s * TS_RESULT_INTS, kvs[s]->result, TS_RESULT_INTS * 4, hipMemcpyDeviceToHost, m->stream));
+  TS_HIP(hipStreamSynchronize(m->stream));
+  m->last_rows = R;
+
+  // ---- hand the result back -----------------------------------------------------------
+  for (int s = 0; s < n_seqs; ++s) {
+    ts_kv* kv = kvs[s];
+    const int32_t* res = m->res_host + (size_t)s * TS_RESULT_INTS;
+    const int len = res[0];
+    const int n = offs[s + 1] - offs[s];
+    if (len < 0 || len > n) return ts_fail(TS_ERR_DEVICE, "device returned accept_len %d for %d nodes", len, n);
+    accept_len[s] = len;
+    bonus[s] = res[1];
+    for (int i = 0; i < len; ++i) {
+      const int row = res[4 + i];
+      acc_tokens[offs[s] + i] = res[4 + TS_MAX_NODES + i];
+      if (acc_nodes) acc_nodes[offs[s] + i] = row - 1;
+      kv->res_rows[i] = row;
+    }
+    kv->res_accept_len = len;
+    kv->res_bonus = res[1];
+    kv->last_M = n + 1;
+    kv->have_result = true;
+  }
+  return TS_OK;
+}
+
+extern "C" ts_status ts_verify(ts_model* m, ts_kv* kv, const int32_t* draft_tokens, const int32_t* parent_idx,
+                               int32_t n_nodes, int32_t* accept_len, int32_t* accepted_tokens, int32_t* accepted_nodes,
+                               int32_t* bonus_token) {
+  if (!m || !kv || !accept_len || !bonus_token || (n_nodes > 0 && !accepted_tokens))
+    return ts_fail(TS_ERR_INVALID_ARG, "ts_verify: null argument");
+  if (n_nodes < 0 || n_nodes > TS_MAX_NODES) return ts_fail(TS_ERR_INVALID_TREE, "n_nodes %d outside [0,%d]", n_nodes, TS_MAX_NODES);
+  const int32_t offs[2] = {0, n_nodes};
+  ts_kv* kvs[1] = {kv};
+  return verify_impl(m, kvs, 1, draft_tokens, parent_idx, offs, accept_len, accepted_tokens, accepted_nodes, bonus_token);
+}
+
+extern "C" ts_status ts_verify_batch(ts_model* m, ts_kv* const* kvs, int32_t n_seqs, const int32_t* draft_tokens,
+                                     const int32_t* parent_idx, const int32_t* node_offsets, int32_t* accept_len,
+                                     int32_t* accepted_tokens, int32_t* accepted_nodes, int32_t* bonus_token) {
+  if (!m || !kvs || !node_offsets || !accept_len || !bonus_token) return ts_fail(TS_ERR_INVALID_ARG, "ts_verify_batch: null argument");
+  if (n_seqs < 1 || n_seqs > 4096) return ts_fail(TS_ERR_INVALID_ARG, "n_seqs %d outside [1,4096]", n_seqs);
+  if (node_offsets[0] != 0) return ts_fail(TS_ERR_INVALID_ARG, "node_offsets[0] must be 0");
+  for (int s = 0; s < n_seqs; ++s)
+    if (node_offsets[s + 1] < node_offsets[s]) return ts_fail(TS_ERR_INVALID_ARG, "node_offsets must be non-decreasing");
+  if (node_offsets[n_seqs] > 0 && !accepted_tokens) return ts_fail(TS_ERR_INVALID_ARG, "null accepted_tokens");
+  return verify_impl(m, kvs, n_seqs, draft_tokens, parent_idx, node_offsets, accept_len, accepted_tokens, accepted_nodes, bonus_token);
+}
+
+// ---------------------------------------------------------------------------------
+// commit
+// ---------------------------------------------------------------------------------
+extern "C" ts_status ts_kv_commit(ts_kv* kv) {
+  if (!kv) return ts_fail(TS_ERR_INVALID_ARG, "null cache");
+  if (!kv->have_result) return ts_fail(TS_ERR_STATE, "no unapplied verify result on this cache");
+  ts_model* m = kv->model;
+  (void)hipSetDevice(m->device);
+  const int len = kv->res_accept_len;
+  bool moves = false;
+  for (int i = 0; i < len; ++i) moves |= (kv->res_rows[i] != i + 1);
+  if (moves) {
+    launch_commit(kv, len);
+    TS_HIP(hipGetLastError());
+    TS_HIP(hipStreamSynchronize(m->stream));
+  }
+  kv->P += len + 1;
+  kv->pending = kv->res_bonus;
+  kv->have_result = false;
+  return TS_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// profiling
+// ---------------------------------------------------------------------------------
+extern "C" ts_status ts_profile_enable(ts_model* m, int32_t enable) {
+  if (!m) return ts_fail(TS_ERR_INVALID_ARG, "null model");
+  m->prof_on = enable != 0;
+  m->prof.clear();
+  m->ev_used = 0;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_entries, int32_t* n_entries) {
+  if (!m || !n_entries || (max_entries > 0 && !entries)) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  (void)hipSetDevice(m->device);
+  TS_HIP(hipStreamSynchronize(m->stream));
+  std::vector<ts_profile_entry> agg;
+  for (const ProfRec& r : m->prof) {
+    float ms = 0.f;
+    TS_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+    size_t i = 0;
+    for (; i < agg.size(); ++i)
+      if (agg[i].name == r.name || strcmp(agg[i].name, r.name) == 0) break;
+    if (i == agg.size()) agg.push_back(ts_profile_entry{r.name, 0, 0.f});
+    agg[i].launches += 1;
+    agg[i].total_ms += ms;
+  }
+  *n_entries = (int32_t)agg.size();
+  for (int i = 0; i < (int)agg.size() && i < max_entries; ++i) entries[i] = agg[i];
+  return TS_OK;
+}

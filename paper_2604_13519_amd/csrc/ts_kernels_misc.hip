@@ -1,0 +1,516 @@
+// Row-wise and bookkeeping kernels of the verify pass, plus the fp32 compute path.
+//
+// Everything here is bandwidth-trivial next to the weight and K/V streams (a verify
+// pass has at most a few hundred rows); the kernels are written for clarity and for
+// few launches.  Storage type T is float (fp32 models) or bf16_t (bf16 models);
+// arithmetic is fp32 everywhere, bf16 only when a value is stored.
+#include "ts_internal.h"
+#include "ts_device_utils.h"
+
+// ---------------------------------------------------------------------------------
+// weight re-tiling (model load): row-major [N][K] bf16 -> MFMA operand tiles.
+// Tile (nt, kt) covers out-features [16 nt, 16 nt + 16) x in-features [32 kt, 32 kt + 32)
+// and is stored as 64 lanes x 8 elements, lane l holding W[16 nt + l%16][32 kt + 8 (l/16) + e],
+// i.e. exactly one wave-wide 16-byte-per-lane load.  Tiles of one nt are contiguous in kt.
+// Destination tile index = n_tile0 + nt * n_tile_stride, which lets two matrices be
+// interleaved tile by tile (gate / up).  Rows >= N are zero-filled.
+// ---------------------------------------------------------------------------------
+__global__ void k_repack_tiles(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                               int N, int K, int n_tile0, int n_tile_stride) {
+  const int kt_count = K / 32;
+  const size_t n_tiles = (size_t)((N + 15) / 16) * kt_count;
+  for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < n_tiles * 64;
+       v += (size_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(v & 63);
+    const size_t tile = v >> 6;
+    const int nt = (int)(tile / kt_count), kt = (int)(tile % kt_count);
+    const int n = nt * 16 + (lane & 15);
+    const int k = kt * 32 + (lane >> 4) * 8;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (n < N) val = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);
+    const size_t dtile = (size_t)(n_tile0 + nt * n_tile_stride) * kt_count + kt;
+    *reinterpret_cast<uint4*>(dst + (dtile * 64 + lane) * 8) = val;
+  }
+}
+
+void launch_repack_tiles(hipStream_t s, const bf16_t* src, bf16_t* dst, int N, int K, int n_tile0,
+                         int n_tile_stride) {
+  size_t vecs = (size_t)((N + 15) / 16) * (K / 32) * 64;
+  int blocks = (int)((vecs + 255) / 256);
+  if (blocks > 65535) blocks = 65535;
+  hipLaunchKernelGGL(k_repack_tiles, dim3(blocks), dim3(256), 0, s, src, dst, N, K, n_tile0, n_tile_stride);
+}
+
+// ---------------------------------------------------------------------------------
+// embedding gather: H[r][:] = E[tok[r]][:]  (residual stream is fp32)
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_embed(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ H, int d) {
+  const int r = blockIdx.x;
+  const T* e = E + (size_t)tok[r] * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) H[(size_t)r * d + i] = ld_f32(e + i);
+}
+
+void launch_embed(ts_model* m, const RowMeta& rm, int R) {
+  ProfScope ps(m, "embed");
+  if (m->cfg.dtype == TS_DTYPE_BF16)
+    hipLaunchKernelGGL(k_embed<bf16_t>, dim3(R), dim3(256), 0, m->stream, (const bf16_t*)m->embed, rm.tok, m->H, m->cfg.d_model);
+  else
+    hipLaunchKernelGGL(k_embed<float>, dim3(R), dim3(256), 0, m->stream, (const float*)m->embed, rm.tok, m->H, m->cfg.d_model);
+}
+
+// ---------------------------------------------------------------------------------
+// rotary table: (cos, sin)(pos[r] * theta^(-2j/hd)) for j < hd/2, evaluated in double so
+// that large positions lose no phase accuracy, stored as float.
+// ---------------------------------------------------------------------------------
+__global__ void k_rope_table(const int32_t* __restrict__ pos, float2* __restrict__ cs, int half, double theta) {
+  const int r = blockIdx.x;
+  for (int j = threadIdx.x; j < half; j += blockDim.x) {
+    const double inv_freq = pow(theta, -(double)j / (double)half);
+    const double ang = (double)pos[r] * inv_freq;
+    cs[(size_t)r * half + j] = make_float2((float)cos(ang), (float)sin(ang));
+  }
+}
+
+void launch_rope_table(ts_model* m, const RowMeta& rm, int R) {
+  ProfScope ps(m, "rope_table");
+  hipLaunchKernelGGL(k_rope_table, dim3(R), dim3(64), 0, m->stream, rm.pos, m->rope_cs, m->cfg.head_dim / 2,
+                     (double)m->cfg.rope_theta);
+}
+
+// ---------------------------------------------------------------------------------
+// residual update + RMSNorm:  H[r] += sum_s part[s][r]  (skipped when n_parts = 0),
+// Xn[r] = T( H[r] * rsqrt(mean(H[r]^2) + eps) * gain ).
+// One block per row.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_norm(float* __restrict__ H, const float* __restrict__ part, int n_parts,
+                                              size_t part_stride, const float* __restrict__ gain,
+                                              T* __restrict__ Xn, int d, float eps) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  float* h = H + (size_t)r * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = h[i];
+    if (n_parts > 0) {
+      float a = 0.f;
+      for (int s = 0; s < n_parts; ++s) a += part[(size_t)s * part_stride + (size_t)r * d + i];
+      v += a;
+      h[i] = v;
+    }
+    ss += v * v;
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = red[0] + red[1] + red[2] + red[3];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) st_from_f32(Xn + (size_t)r * d + i, h[i] * inv * gain[i]);
+}
+
+void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part_stride, bool) {
+  ProfScope ps(m, "residual_rmsnorm");
+  if (m->cfg.dtype == TS_DTYPE_BF16)
+    hipLaunchKernelGGL(k_norm<bf16_t>, dim3(R), dim3(256), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
+                       (bf16_t*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
+  else
+    hipLaunchKernelGGL(k_norm<float>, dim3(R), dim3(256), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
+                       (float*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
+}
+
+// ---------------------------------------------------------------------------------
+// QKV epilogue: sum split-K partials, rotate Q and K at the row's position, store Q for
+// the attention kernel and K / V into the row's tree slot (committed length + local row)
+// of its sequence's paged cache.  K pages are [16 tokens][hd]; V pages are stored
+// transposed, [hd][16 tokens], which is the operand order of the P.V product.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ part, int n_parts, size_t part_stride,
+                                                 const float2* __restrict__ cs, const int32_t* __restrict__ row_seq,
+                                                 const int32_t* __restrict__ row_lrow, const SeqDesc* __restrict__ seqs,
+                                                 T* __restrict__ Qb, int layer, int Hq, int Hkv, int hd) {
+  const int r = blockIdx.x;
+  const int half = hd / 2;
+  const int q_dim = Hq * hd, kv_dim = Hkv * hd, N = q_dim + 2 * kv_dim;
+  const SeqDesc sd = seqs[row_seq[r]];
+  const int slot = sd.P + row_lrow[r];
+  const int phys = sd.page_table[slot >> 4];
+  const int t = slot & 15;
+  const size_t page_elems = (size_t)Hkv * 16 * hd;
+  T* kpage = (T*)sd.k_pool + ((size_t)layer * sd.n_pages + phys) * page_elems;
+  T* vpage = (T*)sd.v_pool + ((size_t)layer * sd.n_pages + phys) * page_elems;
+  const float* p0 = part + (size_t)r * N;
+
+  const int n_pairs = (Hq + Hkv) * half;
+  for (int pi = threadIdx.x; pi < n_pairs; pi += 256) {
+    const int head = pi / half, j = pi % half;
+    const int c1 = head * hd + j, c2 = c1 + half;
+    float x1 = 0.f, x2 = 0.f;
+    for (int s = 0; s < n_parts; ++s) {
+      x1 += p0[(size_t)s * part_stride + c1];
+      x2 += p0[(size_t)s * part_stride + c2];
+    }
+    const float2 w = cs[(size_t)r * half + j];
+    const float y1 = x1 * w.x - x2 * w.y;
+    const float y2 = x2 * w.x + x1 * w.y;
+    if (head < Hq) {
+      st_from_f32(Qb + (size_t)r * q_dim + c1, y1);
+      st_from_f32(Qb + (size_t)r * q_dim + c2, y2);
+    } else {
+      const int g = head - Hq;
+      T* krow = kpage + ((size_t)g * 16 + t) * hd;
+      st_from_f32(krow + j, y1);
+      st_from_f32(krow + j + half, y2);
+    }
+  }
+  for (int vi = threadIdx.x; vi < kv_dim; vi += 256) {
+    const int g = vi / hd, dd = vi % hd;
+    float x = 0.f;
+    for (int s = 0; s < n_parts; ++s) x += p0[(size_t)s * part_stride + q_dim + kv_dim + vi];
+    st_from_f32(vpage + ((size_t)g * hd + dd) * 16 + t, x);
+  }
+}
+
+void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_parts, size_t part_stride) {
+  ProfScope ps(m, "rope_kv_write");
+  const ts_model_config& c = m->cfg;
+  if (c.dtype == TS_DTYPE_BF16)
+    hipLaunchKernelGGL(k_rope_kv<bf16_t>, dim3(R), dim3(256), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
+                       rm.seq, rm.lrow, m->seq_dev, (bf16_t*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
+  else
+    hipLaunchKernelGGL(k_rope_kv<float>, dim3(R), dim3(256), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
+                       rm.seq, rm.lrow, m->seq_dev, (float*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
+}
+
+// ---------------------------------------------------------------------------------
+// SwiGLU: Fb[r][f] = T( silu(gate) * up ), gate / up = sums of split-K partials of the
+// fused projection whose 16-column tiles alternate gate, up, gate, up, ...
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t part_stride, T* __restrict__ Fb, int R,
+                         int F) {
+  const size_t total = (size_t)R * F;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i / F), f = (int)(i % F);
+    const int cg = (f >> 4) * 32 + (f & 15);
+    const float* p = part + (size_t)r * (2 * F) + cg;
+    float g = 0.f, u = 0.f;
+    for (int s = 0; s < n_parts; ++s) {
+      g += p[(size_t)s * part_stride];
+      u += p[(size_t)s * part_stride + 16];
+    }
+    st_from_f32(Fb + i, g / (1.0f + expf(-g)) * u);
+  }
+}
+
+void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride) {
+  ProfScope ps(m, "swiglu");
+  const int F = m->cfg.d_ffn;
+  size_t total = (size_t)R * F;
+  int blocks = (int)((total + 255) / 256);
+  if (blocks > 4096) blocks = 4096;
+  if (m->cfg.dtype == TS_DTYPE_BF16)
+    hipLaunchKernelGGL(k_swiglu<bf16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (bf16_t*)m->Fb, R, F);
+  else
+    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, R, F);
+}
+
+// ---------------------------------------------------------------------------------
+// arg-max over a row of materialised logits (fp32 path): one block per row, one partial.
+// Lowest index wins among equal values.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_argmax_rows(const float* __restrict__ logits, int V, float* __restrict__ aval,
+                                                     int32_t* __restrict__ aidx, int parts) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int r = blockIdx.x;
+  const float* p = logits + (size_t)r * V;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < V; i += 256) amax_take(bv, bi, p[i], i);
+  wave_amax(bv, bi);
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) amax_take(bv, bi, sv[w], si[w]);
+    aval[(size_t)r * parts] = bv;
+    aidx[(size_t)r * parts] = bi;
+  }
+}
+
+void launch_argmax_rows(ts_model* m, int R) {
+  ProfScope ps(m, "argmax_rows");
+  hipLaunchKernelGGL(k_argmax_rows, dim3(R), dim3(256), 0, m->stream, m->logits, m->cfg.vocab, m->amax_val, m->amax_idx, m->amax_parts);
+}
+
+// ---------------------------------------------------------------------------------
+// greedy acceptance walk, one wave per sequence.
+//   g[r]     = arg-max token of row r, combined from `parts` (value, index) partials
+//   valid[r] = valid[parent(r)] && tok[r] == g[parent(r)],  valid[root] = true
+//   best     = deepest valid row, lowest row index among equals
+// result: [0] accept_len, [1] bonus token g[best], [2] best row, [4+i] row of depth i+1,
+//         [4+64+i] token of depth i+1.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_walk(const float* __restrict__ aval, const int32_t* __restrict__ aidx, int parts,
+                                             int used_parts, const int32_t* __restrict__ tok,
+                                             const int32_t* __restrict__ par, const int32_t* __restrict__ depth,
+                                             const SeqDesc* __restrict__ seqs) {
+  __shared__ int g[TS_MAX_NODES + 1];
+  __shared__ unsigned char valid[TS_MAX_NODES + 1];
+  const SeqDesc sd = seqs[blockIdx.x];
+  const int lane = threadIdx.x;
+  for (int r = 0; r < sd.M; ++r) {
+    const size_t base = (size_t)(sd.row0 + r) * parts;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int p = lane; p < used_parts; p += 64) amax_take(bv, bi, aval[base + p], aidx[base + p]);
+    wave_amax(bv, bi);
+    if (lane == 0) g[r] = bi;
+  }
+  __syncthreads();
+  if (lane == 0) {
+    const int32_t* t = tok + sd.row0;
+    const int32_t* pa = par + sd.row0;
+    const int32_t* de = depth + sd.row0;
+    int best = 0;
+    valid[0] = 1;
+    for (int r = 1; r < sd.M; ++r) {
+      const int p = pa[r];
+      const unsigned char v = valid[p] && (t[r] == g[p]);
+      valid[r] = v;
+      if (v && de[r] > de[best]) best = r;
+    }
+    int32_t* res = sd.result;
+    const int len = de[best];
+    res[0] = len;
+    res[1] = g[best];
+    res[2] = best;
+    int r = best;
+    for (int dd = len; dd >= 1; --dd) {
+      res[4 + dd - 1] = r;
+      res[4 + TS_MAX_NODES + dd - 1] = t[r];
+      r = pa[r];
+    }
+  }
+}
+
+void launch_walk(ts_model* m, const RowMeta& rm, int n_seqs) {
+  ProfScope ps(m, "accept_walk");
+  hipLaunchKernelGGL(k_walk, dim3(n_seqs), dim3(64), 0, m->stream, m->amax_val, m->amax_idx, m->amax_parts,
+                     m->amax_parts, rm.tok, rm.par, rm.depth, m->seq_dev);
+}
+
+// ---------------------------------------------------------------------------------
+// commit: move the K/V of the accepted row of depth d from tree slot P + row_d to slot
+// P + d, for d = 1..l.  A thread owns one element column (one head-dim index of one KV
+// head of one layer) across all depths and walks d upwards; since row_d >= d and rows
+// increase with depth, a slot is always read before the step that overwrites it, and no
+// two threads touch the same element, so the in-place move is race-free.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_commit(T* __restrict__ k_pool, T* __restrict__ v_pool, const int32_t* __restrict__ page_table,
+                         const int32_t* __restrict__ result, int n_pages, int Hkv, int hd, int P, int len) {
+  const int layer = blockIdx.x / Hkv, g = blockIdx.x % Hkv;
+  const int dd = threadIdx.x;
+  if (dd >= hd) return;
+  const size_t page_elems = (size_t)Hkv * 16 * hd;
+  for (int dep = 1; dep <= len; ++dep) {
+    const int src = P + result[4 + dep - 1], dst = P + dep;
+    if (src == dst) continue;
+    const size_t sp = ((size_t)layer * n_pages + page_table[src >> 4]) * page_elems;
+    const size_t dp = ((size_t)layer * n_pages + page_table[dst >> 4]) * page_elems;
+    const int st = src & 15, dt = dst & 15;
+    k_pool[dp + ((size_t)g * 16 + dt) * hd + dd] = k_pool[sp + ((size_t)g * 16 + st) * hd + dd];
+    v_pool[dp + ((size_t)g * hd + dd) * 16 + dt] = v_pool[sp + ((size_t)g * hd + dd) * 16 + st];
+  }
+}
+
+void launch_commit(ts_kv* kv, int accept_len) {
+  ts_model* m = kv->model;
+  const ts_model_config& c = m->cfg;
+  dim3 grid(c.n_layers * c.n_kv_heads), block(c.head_dim <= 64 ? 64 : 128);
+  if (c.dtype == TS_DTYPE_BF16)
+    hipLaunchKernelGGL(k_commit<bf16_t>, grid, block, 0, m->stream, (bf16_t*)kv->k_pool, (bf16_t*)kv->v_pool,
+                       kv->page_table, kv->result, kv->n_pages, c.n_kv_heads, c.head_dim, kv->P, accept_len);
+  else
+    hipLaunchKernelGGL(k_commit<float>, grid, block, 0, m->stream, (float*)kv->k_pool, (float*)kv->v_pool,
+                       kv->page_table, kv->result, kv->n_pages, c.n_kv_heads, c.head_dim, kv->P, accept_len);
+}
+
+// ---------------------------------------------------------------------------------
+// import / export between the position-major exchange layout [pos][Hkv][hd] (one layer,
+// staged on the device) and the paged pools.
+// ---------------------------------------------------------------------------------
+template <typename T, bool IMPORT>
+__global__ void k_kv_xfer(T* __restrict__ k_pool, T* __restrict__ v_pool, const int32_t* __restrict__ page_table,
+                          T* __restrict__ sk, T* __restrict__ sv, int layer, int n_pages, int Hkv, int hd, int pos0,
+                          int n_pos) {
+  const size_t page_elems = (size_t)Hkv * 16 * hd;
+  const size_t total = (size_t)n_pos * Hkv * hd;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int dd = (int)(i % hd);
+    const int g = (int)((i / hd) % Hkv);
+    const int pos = pos0 + (int)(i / ((size_t)hd * Hkv));
+    const size_t pg = ((size_t)layer * n_pages + page_table[pos >> 4]) * page_elems;
+    const int t = pos & 15;
+    const size_t ki = pg + ((size_t)g * 16 + t) * hd + dd;
+    const size_t vi = pg + ((size_t)g * hd + dd) * 16 + t;
+    if (IMPORT) { k_pool[ki] = sk[i]; v_pool[vi] = sv[i]; }
+    else        { sk[i] = k_pool[ki]; sv[i] = v_pool[vi]; }
+  }
+}
+
+template <bool IMPORT>
+static void kv_xfer(ts_kv* kv, int pos0, int n_pos, void* sk, void* sv, int layer) {
+  ts_model* m = kv->model;
+  const ts_model_config& c = m->cfg;
+  size_t total = (size_t)n_pos * c.n_kv_heads * c.head_dim;
+  int blocks = (int)((total + 255) / 256);
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  if (c.dtype == TS_DTYPE_BF16)
+    hipLaunchKernelGGL((k_kv_xfer<bf16_t, IMPORT>), dim3(blocks), dim3(256), 0, m->stream, (bf16_t*)kv->k_pool,
+                       (bf16_t*)kv->v_pool, kv->page_table, (bf16_t*)sk, (bf16_t*)sv, layer, kv->n_pages,
+                       c.n_kv_heads, c.head_dim, pos0, n_pos);
+  else
+    hipLaunchKernelGGL((k_kv_xfer<float, IMPORT>), dim3(blocks), dim3(256), 0, m->stream, (float*)kv->k_pool,
+                       (float*)kv->v_pool, kv->page_table, (float*)sk, (float*)sv, layer, kv->n_pages, c.n_kv_heads,
+                       c.head_dim, pos0, n_pos);
+}
+
+void launch_kv_import(ts_kv* kv, int pos0, int n_pos, const void* sk, const void* sv, int layer) {
+  kv_xfer<true>(kv, pos0, n_pos, const_cast<void*>(sk), const_cast<void*>(sv), layer);
+}
+void launch_kv_export(ts_kv* kv, int pos0, int n_pos, void* sk, void* sv, int layer) {
+  kv_xfer<false>(kv, pos0, n_pos, sk, sv, layer);
+}
+
+// =================================================================================
+// fp32 compute path (small models; launch-latency bound, written for exactness)
+// =================================================================================
+
+// out[M][N] = X[M][K] . W[N][K]^T, fp32 FMA in ascending k.  Block = 16 rows x 64 columns.
+__global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ X, const float* __restrict__ W,
+                                                  float* __restrict__ out, int M, int N, int K) {
+  __shared__ float xs[16][33];
+  __shared__ float ws[64][33];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int n0 = blockIdx.x * 64, m0 = blockIdx.y * 16;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < K; k0 += 32) {
+    for (int i = threadIdx.x; i < 16 * 32; i += 256) {
+      const int r = i >> 5, c = i & 31;
+      xs[r][c] = (m0 + r < M && k0 + c < K) ? X[(size_t)(m0 + r) * K + k0 + c] : 0.f;
+    }
+    for (int i = threadIdx.x; i < 64 * 32; i += 256) {
+      const int r = i >> 5, c = i & 31;
+      ws[r][c] = (n0 + r < N && k0 + c < K) ? W[(size_t)(n0 + r) * K + k0 + c] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 32; ++c) {
+      const float w = ws[tx][c];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = fmaf(xs[ty * 4 + i][c], w, acc[i]);
+    }
+    __syncthreads();
+  }
+  for (int i = 0; i < 4; ++i) {
+    const int r = m0 + ty * 4 + i, n = n0 + tx;
+    if (r < M && n < N) out[(size_t)r * N + n] = acc[i];
+  }
+}
+
+void launch_gemm_f32(ts_model* m, const float* X, const float* W, float* out, int M, int N, int K) {
+  ProfScope ps(m, "gemm_f32");
+  hipLaunchKernelGGL(k_gemm_f32, dim3((N + 63) / 64, (M + 15) / 16), dim3(256), 0, m->stream, X, W, out, M, N, K);
+}
+
+// Tree-masked attention, fp32: one block per (row, query head).  Scores for all keys of
+// the row's sequence live in LDS.  Key j < P is context (visible); key P + s is tree row s,
+// visible iff s = 0 (root) or bit s-1 of the row's ancestor mask is set.
+size_t attn_f32_max_keys() { return 15000; }
+
+__global__ __launch_bounds__(256) void k_attn_f32(const float* __restrict__ Qb, float* __restrict__ Ab,
+                                                  const int32_t* __restrict__ row_seq,
+                                                  const int32_t* __restrict__ row_lrow,
+                                                  const uint64_t* __restrict__ row_anc,
+                                                  const SeqDesc* __restrict__ seqs, int layer, int Hq, int Hkv, int hd,
+                                                  float scale) {
+  extern __shared__ float smem[];
+  __shared__ float red[4];
+  const int r = blockIdx.x, h = blockIdx.y, g = h / (Hq / Hkv);
+  const SeqDesc sd = seqs[row_seq[r]];
+  const uint64_t anc = row_anc[r];
+  const int T = sd.P + sd.M;
+  float* q = smem;          // [hd]
+  float* sc = smem + hd;    // [T]
+  float* acc = sc + T;      // [256]
+  const size_t page_elems = (size_t)Hkv * 16 * hd;
+  const float* kl = (const float*)sd.k_pool + (size_t)layer * sd.n_pages * page_elems;
+  const float* vl = (const float*)sd.v_pool + (size_t)layer * sd.n_pages * page_elems;
+  for (int i = threadIdx.x; i < hd; i += 256) q[i] = Qb[(size_t)r * Hq * hd + h * hd + i];
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < T; j += 256) {
+    bool vis = true;
+    if (j >= sd.P) {
+      const int s = j - sd.P;
+      vis = (s == 0) || ((anc >> (s - 1)) & 1ull);
+    }
+    float v = -INFINITY;
+    if (vis) {
+      const float* kr = kl + (size_t)sd.page_table[j >> 4] * page_elems + ((size_t)g * 16 + (j & 15)) * hd;
+      float a = 0.f;
+      for (int i = 0; i < hd; ++i) a = fmaf(q[i], kr[i], a);
+      v = a * scale;
+    }
+    sc[j] = v;
+    mx = fmaxf(mx, v);
+  }
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int j = threadIdx.x; j < T; j += 256) {
+    const float p = expf(sc[j] - mx);
+    sc[j] = p;
+    sum += p;
+  }
+  sum = wave_sum(sum);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  sum = red[0] + red[1] + red[2] + red[3];
+  // P.V: thread (dd, part) accumulates keys part, part + n_parts, ... for head-dim index dd
+  const int n_parts = 256 / hd;
+  const int dd = threadIdx.x % hd, part = threadIdx.x / hd;
+  float a = 0.f;
+  if (part < n_parts) {
+    for (int j = part; j < T; j += n_parts) {
+      const float p = sc[j];
+      if (p != 0.f) {
+        const float* vp = vl + (size_t)sd.page_table[j >> 4] * page_elems + ((size_t)g * hd + dd) * 16 + (j & 15);
+        a = fmaf(p, *vp, a);
+      }
+    }
+  }
+  acc[threadIdx.x] = a;
+  __syncthreads();
+  if (threadIdx.x < hd) {
+    float o = 0.f;
+    for (int p = 0; p < n_parts; ++p) o += acc[p * hd + threadIdx.x];
+    Ab[(size_t)r * Hq * hd + h * hd + threadIdx.x] = o / sum;
+  }
+}
+
+void launch_attn_f32(ts_model* m, const RowMeta& rm, int R, int, int layer, int max_keys) {
+  ProfScope ps(m, "attn_f32");
+  const ts_model_config& c = m->cfg;
+  size_t shmem = (size_t)(c.head_dim + max_keys + 256) * sizeof(float);
+  hipLaunchKernelGGL(k_attn_f32, dim3(R, c.n_q_heads), dim3(256), shmem, m->stream, (const float*)m->Qb, (float*)m->Ab,
+                     rm.seq, rm.lrow, rm.anc, m->seq_dev, layer, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                     1.0f / sqrtf((float)c.head_dim));
+}

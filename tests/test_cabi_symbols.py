@@ -1,0 +1,46 @@
+"""The shared library loads and exports every function include/toolspec.h declares
+(no GPU needed: nothing is called)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "toolspec.h")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", src)))
+
+
+def test_header_declares_the_core_calls():
+    names = _declared_functions()
+    for core in ("ts_model_load", "ts_kv_alloc", "ts_verify", "ts_kv_commit"):
+        assert core in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2604_13519_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2604_13519_amd.build import build_library
+        build_library(verbose=False)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    names = _declared_functions()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(lib, n), "missing export " + n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_binding_refuses_to_run_without_library(tmp_path):
+    from paper_2604_13519_amd import binding
+    saved = binding._lib
+    binding._lib = None
+    try:
+        with pytest.raises(RuntimeError):
+            binding.load_library(str(tmp_path / "nope.so"))
+    finally:
+        binding._lib = saved

@@ -116,6 +116,24 @@ def bfs_tree(greedy, n_nodes, vocab, rng, max_branch=4, max_depth=12, p_keep=0.7
     return np.asarray(toks, np.int32), np.asarray(par, np.int32)
 
 
+def root_token(vocab, P, seed=3456):
+    """Pending (root) token of the synthetic-context workloads: one seeded uniform id."""
+    return int(np.random.default_rng([seed, P]).integers(vocab))
+
+
+def load_greedy(path):
+    """Token ids (first column) of a stored greedy-continuation file; [] if absent."""
+    import os
+    if not os.path.exists(path):
+        return []
+    out = []
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            out.append(int(line.split()[0]))
+    return out
+
+
 def tree_depths(parent_idx):
     """Depth of every draft node (children of the root have depth 1)."""
     d = np.zeros(len(parent_idx), np.int32)
