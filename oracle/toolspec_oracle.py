@@ -28,8 +28,9 @@ Arithmetic: float64 throughout.  Two modes for models stored in bfloat16:
             even, via float32) at the points where the device path stores or
             feeds bf16: normalised activations entering a projection, the
             rotated Q, new K/V cache entries, unnormalised softmax
-            probabilities entering the P.V product, the attention output, and
-            the SwiGLU product.  The residual stream and the logits are never
+            probabilities entering the P.V product (taken relative to the row
+            maximum rounded up to a whole power of two, see forward_tree), the
+            attention output, and the SwiGLU product.  The residual stream and the logits are never
             rounded.  Integer decisions (argmax, acceptance) are compared in
             this mode so both sides decide in the same precision.
 
@@ -47,6 +48,7 @@ import numpy as np
 
 DTYPE_F32 = 0
 DTYPE_BF16 = 1
+LOG2E = 1.4426950408889634
 
 
 # --------------------------------------------------------------------------- #
@@ -183,7 +185,8 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None):
     newK/newV [L][M][Hkv][hd] = the K/V rows of the pass (row r belongs at
     slot P + r until commit).  Does not modify `kv`."""
     cfg = model.cfg
-    rb = bf16_round if (mode == "R" and cfg.dtype == DTYPE_BF16) else (lambda a: a)
+    rounding = mode == "R" and cfg.dtype == DTYPE_BF16
+    rb = bf16_round if rounding else (lambda a: a)
     M = len(tok)
     P = kv.P
     Hq, Hkv, hd = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -213,8 +216,16 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None):
             s_tree = (Q[:, h, :] @ K[:, g, :].T) * scale            # [M][M]  masked
             s_tree = np.where(vis, s_tree, -np.inf)
             s = np.concatenate([s_ctx, s_tree], axis=1)
-            m = np.max(s, axis=1, keepdims=True)
-            p = rb(np.exp(s - m))                                   # masked entries -> 0
+            if rounding:
+                # bf16 probabilities: exponentials relative to the row maximum rounded UP to
+                # a whole power of two.  Rounding to bf16 commutes with scaling by powers of
+                # two, so this is independent of the order in which keys are visited.
+                t = s * LOG2E
+                m = np.ceil(np.max(t, axis=1, keepdims=True))
+                p = rb(np.exp2(t - m))                              # masked entries -> 0
+            else:
+                m = np.max(s, axis=1, keepdims=True)
+                p = np.exp(s - m)                                   # masked entries -> 0
             denom = np.sum(p, axis=1, keepdims=True)
             vals = np.concatenate([Vc, V[:, g, :]], axis=0)         # [P+M][hd]
             A[:, h, :] = (p @ vals) / denom

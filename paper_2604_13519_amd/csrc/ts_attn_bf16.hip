@@ -20,9 +20,13 @@
 //   of two 16-key tiles pack straight into the B operand of
 //   O^T[dim][query] += V^T . P^T  A = V^T tile from LDS.  V pages are stored transposed in
 //                                 the cache ([head_dim][16 tokens]) exactly for this.
-// Soft-max is the usual running-max / rescale recurrence in fp32; probabilities are rounded
-// to bf16 for the second product and the row sum accumulates those rounded values.
+// Soft-max is the running-max / rescale recurrence in fp32 on scores in log2 units, with the
+// reference rounded up to a whole number so that every rescale is an exact power of two;
+// probabilities 2^(s - ref) are rounded to bf16 for the second product and the row sum
+// accumulates those rounded values.
 // Partial (max, sum, O) per split are combined by k_attn_merge.
+#include <stdlib.h>
+
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 
@@ -42,7 +46,7 @@ struct AttnArgs {
   float* part_o;             // [splits][R][Hq][HD]
   float* part_ml;            // [splits][R][Hq][2]
   int layer, Hq, Hkv, R, splits;
-  float scale;
+  float scale;               // 1/sqrt(head_dim) * log2(e): scores are kept in log2 units
 };
 
 union Pack8 {
@@ -198,17 +202,20 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
           for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[kt][mt][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[mt], mx);
+        // the running reference is a whole number (scores are in log2 units): rescaling by
+        // exact powers of two commutes with the bf16 rounding of the probabilities, so the
+        // result does not depend on how keys are blocked or split
+        const float m_new = fmaxf(m_run[mt], ceilf(mx));
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __expf(m_run[mt] - m_use);
+        const float alpha = exp2f(m_run[mt] - m_use);
         m_run[mt] = m_new;
         float psum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 4; r += 2) {
-            const bf16_t p0 = f32_to_bf16(__expf(s[kt][mt][r] - m_use));
-            const bf16_t p1 = f32_to_bf16(__expf(s[kt][mt][r + 1] - m_use));
+            const bf16_t p0 = f32_to_bf16(exp2f(s[kt][mt][r] - m_use));
+            const bf16_t p1 = f32_to_bf16(exp2f(s[kt][mt][r + 1] - m_use));
             psum += bf16_to_f32(p0) + bf16_to_f32(p1);
             pb[mt].u[kt * 2 + (r >> 1)] = (uint32_t)p0 | ((uint32_t)p1 << 16);
           }
@@ -253,7 +260,7 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
   }
 }
 
-// Combine the splits: out = sum_s e^(m_s - m*) O_s / sum_s e^(m_s - m*) l_s, stored as bf16.
+// Combine the splits: out = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s, stored as bf16.
 __global__ void k_attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                              bf16_t* __restrict__ Ab, int R, int Hq, int HD, int splits) {
   const int r = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
@@ -264,7 +271,7 @@ __global__ void k_attn_merge(const float* __restrict__ part_o, const float* __re
     const size_t base = ((size_t)s * R + r) * Hq + h;
     const float ms = part_ml[base * 2];
     if (ms == -INFINITY) continue;
-    const float w = __expf(ms - mstar);
+    const float w = exp2f(ms - mstar);      // both are whole numbers: an exact power of two
     den += w * part_ml[base * 2 + 1];
     num += w * part_o[base * HD + dd];
   }
@@ -304,6 +311,10 @@ int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs) {
   int want = (m->n_cu + per_split - 1) / per_split;
   if (want < 1) want = 1;
   if (want > n_blk) want = n_blk;
+  if (const char* e = getenv("TS_ATTN_MAX_SPLITS")) {   // tuning / debugging knob
+    const int cap = atoi(e);
+    if (cap >= 1 && want > cap) want = cap;
+  }
   const int bps = (n_blk + want - 1) / want;
   return (n_blk + bps - 1) / bps;
 }
@@ -315,7 +326,7 @@ void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int lay
   a.Qb = (const bf16_t*)m->Qb; a.row_anc = rm.anc; a.seqs = m->seq_dev;
   a.part_o = m->attn_part_o; a.part_ml = m->attn_part_ml;
   a.layer = layer; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads; a.R = R; a.splits = splits;
-  a.scale = 1.0f / sqrtf((float)c.head_dim);
+  a.scale = (float)(1.4426950408889634 / sqrt((double)c.head_dim));   // 1/sqrt(hd) * log2(e)
   const int G = c.n_q_heads / c.n_kv_heads;
   const int hb = heads_per_block(G);
   dim3 grid(splits, c.n_kv_heads * (G / hb), n_seqs);
