@@ -23,7 +23,7 @@
 // Soft-max is the running-max / rescale recurrence in fp32 on scores in log2 units, with the
 // reference rounded up to a whole number so that every rescale is an exact power of two;
 // probabilities 2^(s - ref) are rounded to bf16 for the second product and the row sum
-// accumulates those rounded values.
+// accumulates those rounded values (an extra MFMA against an all-ones operand, fp32 exact).
 // Partial (max, sum, O) per split are combined by k_attn_merge.
 #include <stdlib.h>
 
@@ -45,7 +45,7 @@ struct AttnArgs {
   const SeqDesc* seqs;
   float* part_o;             // [splits][R][Hq][HD]
   float* part_ml;            // [splits][R][Hq][2]
-  int layer, Hq, Hkv, R, splits;
+  int layer, Hq, Hkv, R, splits, n_seqs;
   float scale;               // 1/sqrt(head_dim) * log2(e): scores are kept in log2 units
 };
 
@@ -56,33 +56,46 @@ union Pack8 {
 };
 
 template <int HD, int MT, int HB, int RS>
-__global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
+__global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_bf16(AttnArgs a) {
   constexpr int KSQ = HD / 32;            // k-steps of the score product
   constexpr int DT = HD / 16;             // 16-dim tiles of the output
   constexpr int NTHR = 64 * HB * RS;
   constexpr int VPP = 2 * HD;             // 16-byte vectors per K page (and per V page)
-  constexpr int NVEC = 4 * 2 * VPP;       // 16-byte vectors per key block (K and V)
-  constexpr int NV = (NVEC + NTHR - 1) / NTHR;  // staged vectors per thread and block
+  constexpr int VTS = 20;                 // LDS row stride of a transposed V page, in tokens
+  constexpr int VPG = 2 * VPP;            // 16-byte vectors per page, K then V
+  constexpr int JP = (VPG + NTHR - 1) / NTHR;   // staged vectors per thread and page
+  constexpr int NV = 4 * JP;              // staged vectors per thread and key block
   __shared__ __attribute__((aligned(16))) bf16_t ks_[2][KB][HD + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t vs_[2][4][HD][16];
+  // V^T rows are padded to 20 tokens (40 B): 16 lanes reading 8 B from 16 consecutive head-dim
+  // rows then fall into 16 distinct bank pairs (a 32 B stride would put them on 4)
+  __shared__ __attribute__((aligned(16))) bf16_t vs_[2][4][HD][VTS];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, g4 = lane >> 4;
   const int G = a.Hq / a.Hkv;
   const int subs = G / HB;
-  const int g = blockIdx.y / subs;
-  const int h = g * G + (blockIdx.y % subs) * HB + (wave % HB);
+  // Workgroups are dealt to the 8 XCDs round-robin by linear id.  The `subs` workgroups that
+  // share one (sequence, KV head, key split) read the same K/V, so they are given ids that
+  // differ by 8: same XCD, same L2, dispatched back to back.
+  const int bid = blockIdx.x;
+  const int jj = bid >> 3;
+  const int rest = (jj / subs) * 8 + (bid & 7);
+  if (rest >= a.splits * a.Hkv * a.n_seqs) return;
+  const int split = rest % a.splits;
+  const int g = (rest / a.splits) % a.Hkv;
+  const int h = g * G + (jj % subs) * HB + (wave % HB);
   const int tile0 = (wave / HB) * MT;     // first 16-row tile of this wave
-  const SeqDesc sd = a.seqs[blockIdx.z];
+  const SeqDesc sd = a.seqs[rest / (a.splits * a.Hkv)];
   const int P = sd.P, M = sd.M, T = P + M;
   const int n_blk = (T + KB - 1) / KB;
   const int bps = (n_blk + a.splits - 1) / a.splits;
-  const int b0 = blockIdx.x * bps;
+  const int b0 = split * bps;
   const int b1 = min(n_blk, b0 + bps);
 
   const size_t page_elems = (size_t)a.Hkv * 16 * HD;
-  const bf16_t* kl = (const bf16_t*)sd.k_pool + (size_t)a.layer * sd.n_pages * page_elems + (size_t)g * 16 * HD;
-  const bf16_t* vl = (const bf16_t*)sd.v_pool + (size_t)a.layer * sd.n_pages * page_elems + (size_t)g * 16 * HD;
+  const TS_GLOBAL bf16_t* kl = (const TS_GLOBAL bf16_t*)sd.k_pool + (size_t)a.layer * sd.n_pages * page_elems + (size_t)g * 16 * HD;
+  const TS_GLOBAL bf16_t* vl = (const TS_GLOBAL bf16_t*)sd.v_pool + (size_t)a.layer * sd.n_pages * page_elems + (size_t)g * 16 * HD;
+  const TS_GLOBAL int32_t* ptab = (const TS_GLOBAL int32_t*)sd.page_table;
 
   // resident query fragments and ancestor masks of this wave's head
   bf16x8 qf[MT][KSQ];
@@ -106,36 +119,48 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
     for (int dt = 0; dt < DT; ++dt) o[dt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  Pack8 ones;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) ones.u[i] = 0x3f803f80u;   // bf16 1.0 x 8
+
+  // Staging of one key block (4 pages).  The page loop is wave-uniform, so each page-table
+  // entry is one scalar load and the data loads of all four pages go out back to back.
   u32x4 stage[NV];
   auto load_block = [&](int blk) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int v = tid + i * NTHR;
-      const int p = v / (2 * VPP), w = v % (2 * VPP);
+    for (int p = 0; p < 4; ++p) {
       const int lp = blk * 4 + p;
-      u32x4 val = u32x4{0u, 0u, 0u, 0u};
-      if ((NVEC % NTHR == 0 || v < NVEC) && lp < sd.n_pages && lp * 16 < T) {
-        const size_t pg = (size_t)sd.page_table[lp] * page_elems;
-        const bf16_t* src = (w < VPP) ? (kl + pg + (size_t)w * 8) : (vl + pg + (size_t)(w - VPP) * 8);
-        val = *reinterpret_cast<const u32x4*>(src);
+      const bool ok = lp < sd.n_pages && lp * 16 < T;
+      const size_t pg = ok ? (size_t)ptab[lp] * page_elems : 0;
+#pragma unroll
+      for (int j = 0; j < JP; ++j) {
+        const int w = tid + j * NTHR;
+        u32x4 val = u32x4{0u, 0u, 0u, 0u};
+        if (ok && (VPG % NTHR == 0 || w < VPG)) {
+          const TS_GLOBAL bf16_t* src = (w < VPP) ? (kl + pg + (size_t)w * 8) : (vl + pg + (size_t)(w - VPP) * 8);
+          val = *reinterpret_cast<const TS_GLOBAL u32x4*>(src);
+        }
+        stage[p * JP + j] = val;
       }
-      stage[i] = val;
     }
   };
   auto store_block = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int v = tid + i * NTHR;
-      const int p = v / (2 * VPP), w = v % (2 * VPP);
-      if (NVEC % NTHR != 0 && v >= NVEC) continue;
-      if (w < VPP) {
-        const int t = w / (HD / 8), dv = w % (HD / 8);
-        *reinterpret_cast<u32x4*>(&ks_[buf][p * 16 + t][dv * 8]) = stage[i];
-      } else {
-        const int w2 = w - VPP;
-        *reinterpret_cast<u32x4*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8]) = stage[i];
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int j = 0; j < JP; ++j) {
+        const int w = tid + j * NTHR;
+        if (VPG % NTHR != 0 && w >= VPG) continue;
+        if (w < VPP) {
+          const int t = w / (HD / 8), dv = w % (HD / 8);
+          *reinterpret_cast<u32x4*>(&ks_[buf][p * 16 + t][dv * 8]) = stage[p * JP + j];
+        } else {
+          const int w2 = w - VPP;
+          const u32x4 v = stage[p * JP + j];     // 8 tokens; rows are only 8-byte aligned
+          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8]) = u32x2{v.x, v.y};
+          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8 + 4]) = u32x2{v.z, v.w};
+        }
       }
-    }
   };
 
   if (b0 < b1) {
@@ -169,7 +194,7 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
         }
       }
 
-      // ---- scale, mask ---------------------------------------------------------------
+      // ---- mask (only blocks that reach past the committed context) ----------------------
       if (masked) {
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
@@ -181,18 +206,15 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
             for (int mt = 0; mt < MT; ++mt) {
               bool vis = key < T;
               if (vis && srow > 0) vis = (anc[mt] >> (srow - 1)) & 1ull;
-              s[kt][mt][r] = vis ? s[kt][mt][r] * a.scale : -INFINITY;
+              if (!vis) s[kt][mt][r] = -INFINITY;
             }
           }
-      } else {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) s[kt][mt] *= a.scale;
       }
 
-      // ---- running soft-max ------------------------------------------------------------
+      // ---- running soft-max on raw scores; a.scale = log2(e)/sqrt(hd) folds into the exponent ---
       Pack8 pb[MT];
+      float alpha[MT];
+      bool rescale = false;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         float mx = -INFINITY;
@@ -202,29 +224,35 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
           for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[kt][mt][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // the running reference is a whole number (scores are in log2 units): rescaling by
-        // exact powers of two commutes with the bf16 rounding of the probabilities, so the
-        // result does not depend on how keys are blocked or split
-        const float m_new = fmaxf(m_run[mt], ceilf(mx));
+        // the running reference is a whole number (scores in log2 units): rescaling by exact
+        // powers of two commutes with the bf16 rounding of the probabilities, so the result
+        // does not depend on how keys are blocked or split
+        const float m_new = fmaxf(m_run[mt], ceilf(mx * a.scale));
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = exp2f(m_run[mt] - m_use);
+        alpha[mt] = __builtin_amdgcn_exp2f(m_run[mt] - m_use);
+        rescale |= (m_new != m_run[mt]);
         m_run[mt] = m_new;
-        float psum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-          for (int r = 0; r < 4; r += 2) {
-            const bf16_t p0 = f32_to_bf16(exp2f(s[kt][mt][r] - m_use));
-            const bf16_t p1 = f32_to_bf16(exp2f(s[kt][mt][r + 1] - m_use));
-            psum += bf16_to_f32(p0) + bf16_to_f32(p1);
-            pb[mt].u[kt * 2 + (r >> 1)] = (uint32_t)p0 | ((uint32_t)p1 << 16);
-          }
-        l_run[mt] = l_run[mt] * alpha + psum;
+          for (int r = 0; r < 4; r += 2)
+            pb[mt].u[kt * 2 + (r >> 1)] = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s[kt][mt][r], a.scale, -m_use)),
+                                                      __builtin_amdgcn_exp2f(fmaf(s[kt][mt][r + 1], a.scale, -m_use)));
+      }
+      // the reference moves rarely after the first blocks: skip the O rescale when no row's did
+      if (__builtin_amdgcn_ballot_w64(rescale) != 0ull) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt][mt] *= alpha;
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) o[dt][mt] *= alpha[mt];
       }
 
-      // ---- O^T += V^T . P^T --------------------------------------------------------------
+      // ---- O^T += V^T . P^T ; row sums of the rounded probabilities from an all-ones operand ---
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const f32x4 ps = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.v, pb[mt].v, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        l_run[mt] = fmaf(l_run[mt], alpha[mt], ps[0]);
+      }
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         Pack8 va;
@@ -243,12 +271,10 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
   // ---- partial results of this split ---------------------------------------------------
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    float l = l_run[mt];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    const float l = l_run[mt];     // already the sum over all keys (MFMA reduces over the lane groups)
     const int lrow = (tile0 + mt) * 16 + l15;
     if (lrow < M) {
-      const size_t base = ((size_t)blockIdx.x * a.R + sd.row0 + lrow) * a.Hq + h;
+      const size_t base = ((size_t)split * a.R + sd.row0 + lrow) * a.Hq + h;
       if (g4 == 0) {
         a.part_ml[base * 2 + 0] = m_run[mt];
         a.part_ml[base * 2 + 1] = l;
@@ -261,21 +287,41 @@ __global__ __launch_bounds__(64 * HB * RS) void k_attn_bf16(AttnArgs a) {
 }
 
 // Combine the splits: out = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s, stored as bf16.
-__global__ void k_attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                             bf16_t* __restrict__ Ab, int R, int Hq, int HD, int splits) {
-  const int r = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
+__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                    bf16_t* __restrict__ Ab, int R, int Hq, int HD, int splits) {
+  // one (row, head) pair per group of HD/4 threads, 16-byte accesses
+  const int tpp = HD / 4;
+  const size_t n_slots = (size_t)R * Hq;
+  const size_t slot = (size_t)blockIdx.x * (256 / tpp) + threadIdx.x / tpp;
+  const int d4 = threadIdx.x % tpp;
+  if (slot >= n_slots) return;
+  const float2* ml = reinterpret_cast<const float2*>(part_ml);
+  const float4* po = reinterpret_cast<const float4*>(part_o);
   float mstar = -INFINITY;
-  for (int s = 0; s < splits; ++s) mstar = fmaxf(mstar, part_ml[(((size_t)s * R + r) * Hq + h) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const size_t base = ((size_t)s * R + r) * Hq + h;
-    const float ms = part_ml[base * 2];
-    if (ms == -INFINITY) continue;
-    const float w = exp2f(ms - mstar);      // both are whole numbers: an exact power of two
-    den += w * part_ml[base * 2 + 1];
-    num += w * part_o[base * HD + dd];
+  for (int s = 0; s < splits; ++s) mstar = fmaxf(mstar, ml[s * n_slots + slot].x);
+  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+  float den = 0.f;
+  for (int s0 = 0; s0 < splits; s0 += 8) {
+    float2 m8[8];
+    float4 o8[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const size_t base = (size_t)(s0 + u < splits ? s0 + u : s0) * n_slots + slot;
+      m8[u] = ml[base];
+      o8[u] = po[base * tpp + d4];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      // whole-number references: an exact power of two
+      const float w = (s0 + u < splits && m8[u].x != -INFINITY) ? exp2f(m8[u].x - mstar) : 0.f;
+      den += w * m8[u].y;
+      num.x += w * o8[u].x; num.y += w * o8[u].y; num.z += w * o8[u].z; num.w += w * o8[u].w;
+    }
   }
-  Ab[(size_t)r * Hq * HD + (size_t)h * HD + dd] = f32_to_bf16(num / den);
+  uint2 out;
+  out.x = pack_bf16x2(num.x / den, num.y / den);
+  out.y = pack_bf16x2(num.z / den, num.w / den);
+  *reinterpret_cast<uint2*>(Ab + slot * HD + d4 * 4) = out;
 }
 
 // Rows are covered by RS waves per head, MT tiles of 16 rows each: (tiles -> RS x MT)
@@ -299,7 +345,14 @@ void launch_hd(int hb, int tiles, dim3 grid, hipStream_t s, const AttnArgs& a) {
   else launch_hb<HD, 1>(tiles, grid, s, a);
 }
 
-int heads_per_block(int G) { return G >= 4 ? 4 : (G >= 2 ? 2 : 1); }
+// two heads per workgroup: 4 waves of 256 registers, so two workgroups share a CU and one's
+// waits on K/V loads are covered by the other's arithmetic
+int heads_per_block(int G) {
+  static const int pref = getenv("TS_ATTN_HB") ? atoi(getenv("TS_ATTN_HB")) : 4;   // tuning knob
+  int hb = G >= 4 ? 4 : (G >= 2 ? 2 : 1);
+  if (pref == 2 && hb > 2) hb = 2;
+  return hb;
+}
 
 }  // namespace
 
@@ -308,7 +361,8 @@ int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs) {
   const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
   const int per_split = m->cfg.n_kv_heads * (G / heads_per_block(G)) * n_seqs;
   const int n_blk = (max_keys + KB - 1) / KB;
-  int want = (m->n_cu + per_split - 1) / per_split;
+  const int wg_per_cu = heads_per_block(G) <= 2 ? 2 : 1;
+  int want = (wg_per_cu * m->n_cu + per_split - 1) / per_split;
   if (want < 1) want = 1;
   if (want > n_blk) want = n_blk;
   if (const char* e = getenv("TS_ATTN_MAX_SPLITS")) {   // tuning / debugging knob
@@ -329,7 +383,9 @@ void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int lay
   a.scale = (float)(1.4426950408889634 / sqrt((double)c.head_dim));   // 1/sqrt(hd) * log2(e)
   const int G = c.n_q_heads / c.n_kv_heads;
   const int hb = heads_per_block(G);
-  dim3 grid(splits, c.n_kv_heads * (G / hb), n_seqs);
+  a.n_seqs = n_seqs;
+  const int units = splits * c.n_kv_heads * n_seqs;        // (sequence, KV head, key split) triples
+  dim3 grid(((units + 7) / 8) * 8 * (G / hb));
   const int mt = (max_M + 15) / 16;
   if (c.head_dim == 128) launch_hd<128>(hb, mt, grid, m->stream, a);
   else launch_hd<64>(hb, mt, grid, m->stream, a);
@@ -338,6 +394,7 @@ void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int lay
 void launch_attn_merge(ts_model* m, int R, int splits) {
   ProfScope ps(m, "attn_merge");
   const ts_model_config& c = m->cfg;
-  hipLaunchKernelGGL(k_attn_merge, dim3(R, c.n_q_heads), dim3(c.head_dim), 0, m->stream, m->attn_part_o, m->attn_part_ml,
+  const int per_block = 256 / (c.head_dim / 4);
+  hipLaunchKernelGGL(k_attn_merge, dim3((R * c.n_q_heads + per_block - 1) / per_block), dim3(256), 0, m->stream, m->attn_part_o, m->attn_part_ml,
                      (bf16_t*)m->Ab, R, c.n_q_heads, c.head_dim, splits);
 }

@@ -5,6 +5,11 @@
 
 typedef uint16_t bf16_t;
 
+// Pointers that reach a kernel through a descriptor in memory are generic to the compiler and
+// would be accessed with FLAT instructions, whose completion is tied to the LDS counter; casting
+// them to the global address space keeps vector memory and LDS waits independent.
+#define TS_GLOBAL __attribute__((address_space(1)))
+
 __device__ __forceinline__ float bf16_to_f32(bf16_t u) { return __uint_as_float((uint32_t)u << 16); }
 
 // round to nearest even; NaN stays NaN
@@ -13,6 +18,14 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   if ((b & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
   b += 0x7fffu + ((b >> 16) & 1u);
   return (bf16_t)(b >> 16);
+}
+
+// two floats -> packed bf16 pair (low half = a), round to nearest even, one v_cvt_pk_bf16_f32
+typedef __bf16 ts_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float ts_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  const ts_f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, ts_bf16x2));
 }
 
 __device__ __forceinline__ float ld_f32(const float* p) { return *p; }

@@ -5,10 +5,10 @@
 //  * W is pre-tiled at model load into MFMA operand order (see k_repack_tiles): a wave's
 //    16-byte-per-lane global load is one contiguous 1 KiB tile that feeds
 //    v_mfma_f32_16x16x32_bf16 directly as the B operand - no LDS, no shuffles for weights.
-//  * Each wave owns NT tiles of 16 output features and walks its K range in chunks of 128;
-//    the next chunk's weights are in flight (register double buffer) while the current one
+//  * Each wave owns NT tiles of 16 output features and walks its K range in chunks of KC;
+//    the weights of the next PF chunks are in flight (register ring) while the current one
 //    is multiplied.
-//  * The activations X (R x K, tiny) are shared by the 4 waves of a workgroup through a
+//  * The activations X (R x K, tiny) are shared by the WAVES waves of a workgroup through a
 //    double-buffered LDS chunk and read as A operands with 16-byte LDS loads.
 //  * K is split across workgroups (grid.y) so that every CU streams; partial sums go to a
 //    fp32 [split][row][col] buffer that the next row-wise kernel adds up in a fixed order
@@ -25,10 +25,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int KC = TS_GEMM_KC;   // k elements per chunk
-constexpr int KSTEPS = KC / 32;  // MFMA k-steps per chunk
-constexpr int XS = KC + 8;       // LDS row stride in elements (272 B, keeps 16 B alignment)
-
 struct GemmArgs {
   const bf16_t* X;     // [rows][K] row-major, rows padded to a multiple of 16 in memory
   const bf16_t* Wt;    // tiled weights
@@ -44,61 +40,29 @@ struct GemmArgs {
   int amax_parts;
 };
 
-template <int NT>
-__device__ __forceinline__ void load_w(bf16x8 (&w)[NT][KSTEPS], const bf16_t* __restrict__ Wt, const size_t (&tile0)[NT],
-                                       int kt, int lane) {
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int j = 0; j < KSTEPS; ++j)
-      w[t][j] = *reinterpret_cast<const bf16x8*>(Wt + ((tile0[t] + kt + j) * 64 + lane) * 8);
-}
-
-template <int MT>
-__device__ __forceinline__ void load_x(u32x4 (&xr)[MT], const bf16_t* __restrict__ X, int row0, int K, int kbase, int tid) {
-#pragma unroll
-  for (int p = 0; p < MT; ++p)
-    xr[p] = *reinterpret_cast<const u32x4*>(X + (size_t)(row0 + p * 16 + (tid >> 4)) * K + kbase + (tid & 15) * 8);
-}
-
-template <int MT>
-__device__ __forceinline__ void store_x(bf16_t (*xs)[XS], const u32x4 (&xr)[MT], int tid) {
-#pragma unroll
-  for (int p = 0; p < MT; ++p) *reinterpret_cast<u32x4*>(&xs[p * 16 + (tid >> 4)][(tid & 15) * 8]) = xr[p];
-}
-
-template <int MT, int NT>
-__device__ __forceinline__ void mma_chunk(f32x4 (&acc)[MT][NT], const bf16_t (*xs)[XS], const bf16x8 (&w)[NT][KSTEPS],
-                                          int lane) {
-  const int l15 = lane & 15, g = lane >> 4;
-#pragma unroll
-  for (int ks = 0; ks < KSTEPS; ++ks) {
-    bf16x8 a[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) a[mt] = *reinterpret_cast<const bf16x8*>(&xs[mt * 16 + l15][ks * 32 + g * 8]);
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], w[t][ks], acc[mt][t], 0, 0, 0);
-  }
-}
-
-template <int MT, int NT, bool ARGMAX>
-__global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
+template <int MT, int NT, int WAVES, int KC, int PF, bool ARGMAX>
+__global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
+  constexpr int KSTEPS = KC / 32;           // MFMA k-steps per chunk
+  constexpr int XS = KC + 8;                // LDS row stride in elements (+16 B: bank spread, keeps alignment)
+  constexpr int NTHR = 64 * WAVES;
+  constexpr int NBUF = PF + 1;              // weight register ring
+  constexpr int XV = MT * 16 * KC / 8;      // 16-byte vectors per X chunk
+  constexpr int XPT = (XV + NTHR - 1) / NTHR;
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16][XS];
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l15 = lane & 15, g = lane >> 4;
   const int row0 = blockIdx.z * TS_MROWS_PER_BLOCK;
   const int kbase0 = blockIdx.y * a.kper;
   const int n_chunks = a.kper / KC;
 
-  size_t tile0[NT];
+  const bf16_t* wp[NT];                     // this lane's pointer into each owned tile row
   int nt_idx[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    nt_idx[t] = (blockIdx.x * 4 + wave) * NT + t;
-    const int c = nt_idx[t] < a.n_tiles ? nt_idx[t] : a.n_tiles - 1;   // clamp: idle waves re-read a valid tile
-    tile0[t] = (size_t)c * a.kt_count;
+    nt_idx[t] = (blockIdx.x * WAVES + wave) * NT + t;
+    const int c = nt_idx[t] < a.n_tiles ? nt_idx[t] : a.n_tiles - 1;   // idle waves re-read a valid tile
+    wp[t] = a.Wt + (((size_t)c * a.kt_count + kbase0 / 32) * 64 + lane) * 8;
   }
 
   f32x4 acc[MT][NT];
@@ -107,36 +71,76 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 w0[NT][KSTEPS], w1[NT][KSTEPS];
-  u32x4 xr[MT];
+  bf16x8 w[NBUF][NT][KSTEPS];
+  u32x4 xr[XPT];
 
-  load_w<NT>(w0, a.Wt, tile0, kbase0 / 32, lane);
-  load_x<MT>(xr, a.X, row0, a.K, kbase0, tid);
-  store_x<MT>(xs[0], xr, tid);
+  auto load_w = [&](bf16x8 (&dst)[NT][KSTEPS], int chunk) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int j = 0; j < KSTEPS; ++j)
+        dst[t][j] = __builtin_nontemporal_load(
+            reinterpret_cast<const bf16x8*>(wp[t] + ((size_t)chunk * KSTEPS + j) * 512));
+  };
+  auto load_x = [&](int chunk) {
+    const int kb = kbase0 + chunk * KC;
+#pragma unroll
+    for (int p = 0; p < XPT; ++p) {
+      const int v = tid + p * NTHR;
+      if (XV % NTHR == 0 || v < XV) {
+        const int row = v / (KC / 8), cv = v % (KC / 8);
+        xr[p] = *reinterpret_cast<const u32x4*>(a.X + (size_t)(row0 + row) * a.K + kb + cv * 8);
+      }
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < XPT; ++p) {
+      const int v = tid + p * NTHR;
+      if (XV % NTHR == 0 || v < XV) {
+        const int row = v / (KC / 8), cv = v % (KC / 8);
+        *reinterpret_cast<u32x4*>(&xs[buf][row][cv * 8]) = xr[p];
+      }
+    }
+  };
+  auto mma_chunk = [&](const bf16x8 (&wc)[NT][KSTEPS], int buf) {
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      bf16x8 af[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][mt * 16 + l15][ks * 32 + g * 8]);
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
+    }
+  };
+
+  // prologue: first PF weight chunks in flight, first X chunk staged
+#pragma unroll
+  for (int b = 0; b < PF; ++b)
+    if (b < n_chunks) load_w(w[b], b);
+  load_x(0);
+  store_x(0);
   __syncthreads();
 
-  // two chunks per trip so that the weight register buffers swap without copies
-  int c = 0;
-  for (; c + 1 < n_chunks; c += 2) {
-    const int kb1 = kbase0 + (c + 1) * KC;
-    load_w<NT>(w1, a.Wt, tile0, kb1 / 32, lane);
-    load_x<MT>(xr, a.X, row0, a.K, kb1, tid);
-    mma_chunk<MT, NT>(acc, xs[0], w0, lane);
-    store_x<MT>(xs[1], xr, tid);
-    __syncthreads();
-    const bool more = c + 2 < n_chunks;
-    if (more) {
-      const int kb2 = kbase0 + (c + 2) * KC;
-      load_w<NT>(w0, a.Wt, tile0, kb2 / 32, lane);
-      load_x<MT>(xr, a.X, row0, a.K, kb2, tid);
+  // NBUF chunks per trip so that ring slots are compile-time register names
+  for (int c0 = 0; c0 < n_chunks; c0 += NBUF) {
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b) {
+      const int c = c0 + b;
+      if (c < n_chunks) {
+        if (c + PF < n_chunks) load_w(w[(b + PF) % NBUF], c + PF);
+        const bool more = c + 1 < n_chunks;
+        if (more) load_x(c + 1);
+        mma_chunk(w[b], c & 1);
+        if (more) store_x((c + 1) & 1);
+        __syncthreads();
+      }
     }
-    mma_chunk<MT, NT>(acc, xs[1], w1, lane);
-    if (more) store_x<MT>(xs[0], xr, tid);
-    __syncthreads();
   }
-  if (c < n_chunks) mma_chunk<MT, NT>(acc, xs[0], w0, lane);   // odd chunk count: last chunk sits in buffer 0
 
-  const int l15 = lane & 15, g = lane >> 4;
   if (!ARGMAX) {
     float* o = a.out + (size_t)blockIdx.y * a.split_stride;
 #pragma unroll
@@ -153,8 +157,8 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
       }
     }
   } else {
-    __shared__ float rv[4][MT * 16];
-    __shared__ int ri[4][MT * 16];
+    __shared__ float rv[WAVES][MT * 16];
+    __shared__ int ri[WAVES][MT * 16];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -183,42 +187,70 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmArgs a) {
     if (tid < MT * 16 && row0 + tid < a.R) {
       float bv = rv[0][tid];
       int bi = ri[0][tid];
-      for (int w = 1; w < 4; ++w) amax_take(bv, bi, rv[w][tid], ri[w][tid]);
+      for (int wv = 1; wv < WAVES; ++wv) amax_take(bv, bi, rv[wv][tid], ri[wv][tid]);
       a.aval[(size_t)(row0 + tid) * a.amax_parts + blockIdx.x] = bv;
       a.aidx[(size_t)(row0 + tid) * a.amax_parts + blockIdx.x] = bi;
     }
   }
 }
 
-template <int NT, bool ARGMAX>
+template <int NT, int WAVES, int KC, int PF, bool ARGMAX>
 void launch_mt(int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
   switch (mt) {
-    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, NT, ARGMAX>), grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, NT, ARGMAX>), grid, dim3(256), 0, s, a); break;
-    case 3: hipLaunchKernelGGL((k_gemm_bf16<3, NT, ARGMAX>), grid, dim3(256), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, NT, ARGMAX>), grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<5, NT, ARGMAX>), grid, dim3(256), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
+    case 3: hipLaunchKernelGGL((k_gemm_bf16<3, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<5, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
+  }
+}
+
+// The compiled tile shapes.  shape id -> (NT, WAVES, KC, PF).
+constexpr int kNumShapes = 4;
+const int kShapeNT[kNumShapes] = {1, 2, 1, 2};
+const int kShapeWaves[kNumShapes] = {4, 4, 8, 8};
+const int kShapeKC[kNumShapes] = {128, 128, 256, 256};
+
+template <bool ARGMAX>
+void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
+  switch (shape) {
+    case 0: launch_mt<1, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
+    case 1: launch_mt<2, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
+    case 2: launch_mt<1, 8, 256, 1, ARGMAX>(mt, grid, s, a); break;
+    default: launch_mt<2, 8, 256, 1, ARGMAX>(mt, grid, s, a); break;
   }
 }
 
 }  // namespace
 
-// Tiles per wave and K splits: enough workgroups that every CU holds several, each still
-// walking at least two chunks.
-GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K) {
-  const int n_tiles = (N + 15) / 16;
-  const int chunks = K / KC;
-  GemmPlan p;
-  p.nt = ((n_tiles + 7) / 8 >= m->n_cu) ? 2 : 1;
-  const int groups = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
-  p.splits = 1;
-  for (int s = 1; s <= chunks; ++s) {
-    if (chunks % s) continue;
-    if (chunks / s < 2 && s > 1) break;
-    p.splits = s;
-    if (groups * s >= 2 * m->n_cu) break;
+int gemm_bf16_cols_per_group(int shape) { return kShapeNT[shape] * kShapeWaves[shape] * 16; }
+int gemm_bf16_chunk(int shape) { return kShapeKC[shape]; }
+
+// Tile shape and K splits.  Measured on MI355X, the stream is fastest when the workgroups
+// of a launch fit the chip in ONE round (one 8-wave workgroup per CU): a second round adds
+// a tail and more partial-sum traffic than it gains.  So: the (shape, splits) pair with the
+// most workgroups not exceeding the CU count, wider tiles winning ties; if even the
+// coarsest split exceeds the chip (lm_head), the fewest workgroups.
+GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K, bool allow_split) {
+  GemmPlan best{0, 1};
+  long best_score = -1;
+  for (int shape = 0; shape < kNumShapes; ++shape) {
+    const int kc = kShapeKC[shape];
+    if (K % kc) continue;
+    const int chunks = K / kc;
+    const int cols = gemm_bf16_cols_per_group(shape);
+    const int groups = (N + cols - 1) / cols;
+    for (int s = 1; s <= chunks && s <= 16; ++s) {
+      if (chunks % s) continue;
+      if (!allow_split && s > 1) break;
+      const long wgs = (long)groups * s;
+      // fits in one round: more workgroups is better; otherwise fewer is better
+      long score = wgs <= m->n_cu ? (1L << 40) + wgs * 16 : (1L << 30) - wgs * 16;
+      score += kShapeWaves[shape] + kShapeNT[shape];        // prefer 8 waves, 2 tiles on ties
+      if (score > best_score) { best_score = score; best.shape = shape; best.splits = s; }
+    }
   }
-  return p;
+  return best;
 }
 
 void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, GemmPlan plan,
@@ -233,13 +265,11 @@ void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out
   a.kt_count = K / 32;
   a.split_stride = (size_t)R * N;
   a.amax_parts = m->amax_parts;
-  const int groups = (a.n_tiles + 4 * plan.nt - 1) / (4 * plan.nt);
+  const int cols = gemm_bf16_cols_per_group(plan.shape);
+  const int groups = (N + cols - 1) / cols;
   const int m_blocks = (R + TS_MROWS_PER_BLOCK - 1) / TS_MROWS_PER_BLOCK;
   const int mt = m_blocks > 1 ? 5 : (R + 15) / 16;
   dim3 grid(groups, splits, m_blocks);
-  if (argmax) {
-    if (plan.nt == 2) launch_mt<2, true>(mt, grid, m->stream, a); else launch_mt<1, true>(mt, grid, m->stream, a);
-  } else {
-    if (plan.nt == 2) launch_mt<2, false>(mt, grid, m->stream, a); else launch_mt<1, false>(mt, grid, m->stream, a);
-  }
+  if (argmax) launch_shape<true>(plan.shape, mt, grid, m->stream, a);
+  else launch_shape<false>(plan.shape, mt, grid, m->stream, a);
 }

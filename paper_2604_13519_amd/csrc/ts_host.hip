@@ -98,6 +98,7 @@ static ts_status check_config(const ts_model_config& c) {
   if (c.n_q_heads % c.n_kv_heads) return ts_fail(TS_ERR_INVALID_ARG, "n_q_heads must be a multiple of n_kv_heads");
   if (!(c.rms_eps > 0.f) || !(c.rope_theta > 0.f)) return ts_fail(TS_ERR_INVALID_ARG, "rms_eps and rope_theta must be positive");
   if (c.d_ffn % 16) return ts_fail(TS_ERR_INVALID_ARG, "d_ffn must be a multiple of 16");
+  if (c.d_model % 4) return ts_fail(TS_ERR_INVALID_ARG, "d_model must be a multiple of 4");
   if (c.dtype == TS_DTYPE_BF16) {
     if (c.d_model % 128 || (c.n_q_heads * c.head_dim) % 128 || c.d_ffn % 128)
       return ts_fail(TS_ERR_INVALID_ARG, "bf16 path: d_model, n_q_heads*head_dim and d_ffn must be multiples of 128");
@@ -148,7 +149,7 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs) {
     if (c.dtype == TS_DTYPE_BF16) {
       const int Ns[4] = {m->qkv_dim, c.d_model, 2 * c.d_ffn, c.d_model};
       const int Ks[4] = {c.d_model, m->q_dim, c.d_model, c.d_ffn};
-      for (int i = 0; i < 4; ++i) pe = std::max(pe, (size_t)gemm_bf16_plan(m, Ns[i], Ks[i]).splits * cap * Ns[i]);
+      for (int i = 0; i < 4; ++i) pe = std::max(pe, (size_t)gemm_bf16_plan(m, Ns[i], Ks[i], true).splits * cap * Ns[i]);
     } else {
       pe = (size_t)cap * std::max(std::max(m->qkv_dim, 2 * c.d_ffn), c.d_model);
     }
@@ -337,9 +338,9 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   }
   m->n_cu = prop.multiProcessorCount;
   if (cfg->dtype == TS_DTYPE_BF16) {
-    const GemmPlan p = gemm_bf16_plan(m, cfg->vocab, cfg->d_model);
-    const int n_tiles = (cfg->vocab + 15) / 16;
-    m->amax_parts = (n_tiles + 4 * p.nt - 1) / (4 * p.nt);
+    const GemmPlan p = gemm_bf16_plan(m, cfg->vocab, cfg->d_model, false);
+    const int cols = gemm_bf16_cols_per_group(p.shape);
+    m->amax_parts = (cfg->vocab + cols - 1) / cols;
   } else {
     m->amax_parts = 1;
   }
@@ -603,7 +604,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   size_t pending_stride = 0;
   auto project = [&](const char* name, const void* X, const void* W, int N, int K, int* n_parts, size_t* stride) {
     if (bf) {
-      const GemmPlan p = gemm_bf16_plan(m, N, K);
+      const GemmPlan p = gemm_bf16_plan(m, N, K, true);
       ProfScope ps(m, name);
       launch_gemm_bf16(m, (const bf16_t*)X, (const bf16_t*)W, m->part, R, N, K, p, false, nullptr);
       *n_parts = p.splits;
@@ -634,7 +635,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   }
   launch_norm(m, R, m->norm_f, pending_parts, pending_stride, false);
   if (bf) {
-    const GemmPlan p = gemm_bf16_plan(m, c.vocab, d);
+    const GemmPlan p = gemm_bf16_plan(m, c.vocab, d, false);
     ProfScope ps(m, "gemm_lm_head_argmax");
     launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)m->lm_head, nullptr, R, c.vocab, d, p, true,
                      m->keep_logits ? m->logits : nullptr);

@@ -127,8 +127,10 @@ void launch_gemm_f32(ts_model* m, const float* X, const float* W, float* out, in
 void launch_attn_f32(ts_model* m, const RowMeta& rm, int R, int n_seqs, int layer, int max_keys);
 size_t attn_f32_max_keys();
 // bf16 compute path (ts_gemm_bf16.hip / ts_attn_bf16.hip)
-struct GemmPlan { int nt; int splits; };
-GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K);
+struct GemmPlan { int shape; int splits; };   // compiled tile shape id, K splits
+GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K, bool allow_split);
+int gemm_bf16_cols_per_group(int shape);
+int gemm_bf16_chunk(int shape);
 void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K,
                       GemmPlan plan, bool argmax, float* logits);
 int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs);

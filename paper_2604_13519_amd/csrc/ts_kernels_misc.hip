@@ -81,41 +81,60 @@ void launch_rope_table(ts_model* m, const RowMeta& rm, int R) {
 // ---------------------------------------------------------------------------------
 // residual update + RMSNorm:  H[r] += sum_s part[s][r]  (skipped when n_parts = 0),
 // Xn[r] = T( H[r] * rsqrt(mean(H[r]^2) + eps) * gain ).
-// One block per row.
+// One block of 1024 threads per row, 16-byte accesses; needs d_model % 4 == 0.
 // ---------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void k_norm(float* __restrict__ H, const float* __restrict__ part, int n_parts,
-                                              size_t part_stride, const float* __restrict__ gain,
-                                              T* __restrict__ Xn, int d, float eps) {
-  __shared__ float red[4];
+__global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const float* __restrict__ part, int n_parts,
+                                               size_t part_stride, const float* __restrict__ gain,
+                                               T* __restrict__ Xn, int d, float eps) {
+  __shared__ float red[16];
   const int r = blockIdx.x;
-  float* h = H + (size_t)r * d;
+  float4* h4 = reinterpret_cast<float4*>(H + (size_t)r * d);
+  const float4* p4 = reinterpret_cast<const float4*>(part + (size_t)r * d);
+  const size_t stride4 = part_stride / 4;
+  const int d4 = d / 4;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = h[i];
+  for (int i = threadIdx.x; i < d4; i += 1024) {
+    float4 v = h4[i];
     if (n_parts > 0) {
-      float a = 0.f;
-      for (int s = 0; s < n_parts; ++s) a += part[(size_t)s * part_stride + (size_t)r * d + i];
-      v += a;
-      h[i] = v;
+      // all partial loads of a batch are issued before the first add (fixed summation order)
+      for (int s0 = 0; s0 < n_parts; s0 += 8) {
+        float4 q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          q[j] = (s0 + j < n_parts) ? p4[(size_t)(s0 + j) * stride4 + i] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { v.x += q[j].x; v.y += q[j].y; v.z += q[j].z; v.w += q[j].w; }
+      }
+      h4[i] = v;
     }
-    ss += v * v;
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  const float tot = red[0] + red[1] + red[2] + red[3];
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) tot += red[w];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) st_from_f32(Xn + (size_t)r * d + i, h[i] * inv * gain[i]);
+  const float4* g4 = reinterpret_cast<const float4*>(gain);
+  for (int i = threadIdx.x; i < d4; i += 1024) {
+    const float4 v = h4[i], g = g4[i];
+    T* o = Xn + (size_t)r * d + 4 * i;
+    st_from_f32(o + 0, v.x * inv * g.x);
+    st_from_f32(o + 1, v.y * inv * g.y);
+    st_from_f32(o + 2, v.z * inv * g.z);
+    st_from_f32(o + 3, v.w * inv * g.w);
+  }
 }
 
 void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part_stride, bool) {
   ProfScope ps(m, "residual_rmsnorm");
   if (m->cfg.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_norm<bf16_t>, dim3(R), dim3(256), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
+    hipLaunchKernelGGL(k_norm<bf16_t>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
                        (bf16_t*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
   else
-    hipLaunchKernelGGL(k_norm<float>, dim3(R), dim3(256), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
+    hipLaunchKernelGGL(k_norm<float>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
                        (float*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
 }
 
@@ -126,49 +145,51 @@ void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part
 // transposed, [hd][16 tokens], which is the operand order of the P.V product.
 // ---------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ part, int n_parts, size_t part_stride,
-                                                 const float2* __restrict__ cs, const int32_t* __restrict__ row_seq,
-                                                 const int32_t* __restrict__ row_lrow, const SeqDesc* __restrict__ seqs,
-                                                 T* __restrict__ Qb, int layer, int Hq, int Hkv, int hd) {
-  const int r = blockIdx.x;
+__global__ __launch_bounds__(64) void k_rope_kv(const float* __restrict__ part, int n_parts, size_t part_stride,
+                                                const float2* __restrict__ cs, const int32_t* __restrict__ row_seq,
+                                                const int32_t* __restrict__ row_lrow, const SeqDesc* __restrict__ seqs,
+                                                T* __restrict__ Qb, int layer, int Hq, int Hkv, int hd) {
+  const int r = blockIdx.x, head = blockIdx.y;      // heads: Hq query, then Hkv key, then Hkv value
   const int half = hd / 2;
-  const int q_dim = Hq * hd, kv_dim = Hkv * hd, N = q_dim + 2 * kv_dim;
+  const int q_dim = Hq * hd, N = q_dim + 2 * Hkv * hd;
+  const int j = threadIdx.x;
+  if (j >= half) return;
+  const int c1 = head * hd + j, c2 = c1 + half;
+  const float* p0 = part + (size_t)r * N;
+  float x1 = 0.f, x2 = 0.f;
+  for (int s0 = 0; s0 < n_parts; s0 += 8) {
+    float a[8], b[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const bool ok = s0 + u < n_parts;
+      a[u] = ok ? p0[(size_t)(s0 + u) * part_stride + c1] : 0.f;
+      b[u] = ok ? p0[(size_t)(s0 + u) * part_stride + c2] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { x1 += a[u]; x2 += b[u]; }
+  }
+  if (head < Hq) {
+    const float2 w = cs[(size_t)r * half + j];
+    st_from_f32(Qb + (size_t)r * q_dim + c1, x1 * w.x - x2 * w.y);
+    st_from_f32(Qb + (size_t)r * q_dim + c2, x2 * w.x + x1 * w.y);
+    return;
+  }
   const SeqDesc sd = seqs[row_seq[r]];
   const int slot = sd.P + row_lrow[r];
-  const int phys = sd.page_table[slot >> 4];
   const int t = slot & 15;
   const size_t page_elems = (size_t)Hkv * 16 * hd;
-  T* kpage = (T*)sd.k_pool + ((size_t)layer * sd.n_pages + phys) * page_elems;
-  T* vpage = (T*)sd.v_pool + ((size_t)layer * sd.n_pages + phys) * page_elems;
-  const float* p0 = part + (size_t)r * N;
-
-  const int n_pairs = (Hq + Hkv) * half;
-  for (int pi = threadIdx.x; pi < n_pairs; pi += 256) {
-    const int head = pi / half, j = pi % half;
-    const int c1 = head * hd + j, c2 = c1 + half;
-    float x1 = 0.f, x2 = 0.f;
-    for (int s = 0; s < n_parts; ++s) {
-      x1 += p0[(size_t)s * part_stride + c1];
-      x2 += p0[(size_t)s * part_stride + c2];
-    }
+  const size_t pg = ((size_t)layer * sd.n_pages + sd.page_table[slot >> 4]) * page_elems;
+  if (head < Hq + Hkv) {
+    const int g = head - Hq;
     const float2 w = cs[(size_t)r * half + j];
-    const float y1 = x1 * w.x - x2 * w.y;
-    const float y2 = x2 * w.x + x1 * w.y;
-    if (head < Hq) {
-      st_from_f32(Qb + (size_t)r * q_dim + c1, y1);
-      st_from_f32(Qb + (size_t)r * q_dim + c2, y2);
-    } else {
-      const int g = head - Hq;
-      T* krow = kpage + ((size_t)g * 16 + t) * hd;
-      st_from_f32(krow + j, y1);
-      st_from_f32(krow + j + half, y2);
-    }
-  }
-  for (int vi = threadIdx.x; vi < kv_dim; vi += 256) {
-    const int g = vi / hd, dd = vi % hd;
-    float x = 0.f;
-    for (int s = 0; s < n_parts; ++s) x += p0[(size_t)s * part_stride + q_dim + kv_dim + vi];
-    st_from_f32(vpage + ((size_t)g * hd + dd) * 16 + t, x);
+    T* krow = (T*)sd.k_pool + pg + ((size_t)g * 16 + t) * hd;
+    st_from_f32(krow + j, x1 * w.x - x2 * w.y);
+    st_from_f32(krow + j + half, x2 * w.x + x1 * w.y);
+  } else {
+    const int g = head - Hq - Hkv;
+    T* vcol = (T*)sd.v_pool + pg + (size_t)g * hd * 16 + t;
+    st_from_f32(vcol + (size_t)j * 16, x1);
+    st_from_f32(vcol + (size_t)(j + half) * 16, x2);
   }
 }
 
@@ -176,10 +197,10 @@ void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_part
   ProfScope ps(m, "rope_kv_write");
   const ts_model_config& c = m->cfg;
   if (c.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_rope_kv<bf16_t>, dim3(R), dim3(256), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
+    hipLaunchKernelGGL(k_rope_kv<bf16_t>, dim3(R, c.n_q_heads + 2 * c.n_kv_heads), dim3(64), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
                        rm.seq, rm.lrow, m->seq_dev, (bf16_t*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
   else
-    hipLaunchKernelGGL(k_rope_kv<float>, dim3(R), dim3(256), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
+    hipLaunchKernelGGL(k_rope_kv<float>, dim3(R, c.n_q_heads + 2 * c.n_kv_heads), dim3(64), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
                        rm.seq, rm.lrow, m->seq_dev, (float*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
 }
 
@@ -245,22 +266,22 @@ void launch_argmax_rows(ts_model* m, int R) {
 }
 
 // ---------------------------------------------------------------------------------
-// greedy acceptance walk, one wave per sequence.
+// greedy acceptance walk, one block (16 waves) per sequence.
 //   g[r]     = arg-max token of row r, combined from `parts` (value, index) partials
 //   valid[r] = valid[parent(r)] && tok[r] == g[parent(r)],  valid[root] = true
 //   best     = deepest valid row, lowest row index among equals
 // result: [0] accept_len, [1] bonus token g[best], [2] best row, [4+i] row of depth i+1,
 //         [4+64+i] token of depth i+1.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_walk(const float* __restrict__ aval, const int32_t* __restrict__ aidx, int parts,
-                                             int used_parts, const int32_t* __restrict__ tok,
-                                             const int32_t* __restrict__ par, const int32_t* __restrict__ depth,
-                                             const SeqDesc* __restrict__ seqs) {
+__global__ __launch_bounds__(1024) void k_walk(const float* __restrict__ aval, const int32_t* __restrict__ aidx, int parts,
+                                               int used_parts, const int32_t* __restrict__ tok,
+                                               const int32_t* __restrict__ par, const int32_t* __restrict__ depth,
+                                               const SeqDesc* __restrict__ seqs) {
   __shared__ int g[TS_MAX_NODES + 1];
   __shared__ unsigned char valid[TS_MAX_NODES + 1];
   const SeqDesc sd = seqs[blockIdx.x];
-  const int lane = threadIdx.x;
-  for (int r = 0; r < sd.M; ++r) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int r = wave; r < sd.M; r += 16) {            // one wave per row, lanes stride over the partials
     const size_t base = (size_t)(sd.row0 + r) * parts;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
@@ -269,7 +290,7 @@ __global__ __launch_bounds__(64) void k_walk(const float* __restrict__ aval, con
     if (lane == 0) g[r] = bi;
   }
   __syncthreads();
-  if (lane == 0) {
+  if (threadIdx.x == 0) {
     const int32_t* t = tok + sd.row0;
     const int32_t* pa = par + sd.row0;
     const int32_t* de = depth + sd.row0;
@@ -297,7 +318,7 @@ __global__ __launch_bounds__(64) void k_walk(const float* __restrict__ aval, con
 
 void launch_walk(ts_model* m, const RowMeta& rm, int n_seqs) {
   ProfScope ps(m, "accept_walk");
-  hipLaunchKernelGGL(k_walk, dim3(n_seqs), dim3(64), 0, m->stream, m->amax_val, m->amax_idx, m->amax_parts,
+  hipLaunchKernelGGL(k_walk, dim3(n_seqs), dim3(1024), 0, m->stream, m->amax_val, m->amax_idx, m->amax_parts,
                      m->amax_parts, rm.tok, rm.par, rm.depth, m->seq_dev);
 }
 
