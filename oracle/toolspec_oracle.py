@@ -26,12 +26,16 @@ Arithmetic: float64 throughout.  Two modes for models stored in bfloat16:
   mode "E"  exact float64 math on the stored (bf16-valued) weights and context.
   mode "R"  same float64 math, but values are rounded to bfloat16 (nearest
             even, via float32) at the points where the device path stores or
-            feeds bf16: normalised activations entering a projection, the
-            rotated Q, new K/V cache entries, unnormalised softmax
-            probabilities entering the P.V product (taken relative to the row
-            maximum rounded up to a whole power of two, see forward_tree), the
-            attention output, and the SwiGLU product.  The residual stream and the logits are never
-            rounded.  Integer decisions (argmax, acceptance) are compared in
+            feeds 16-bit values.  bf16: new K/V cache entries.  IEEE half (the
+            attention products run in half precision; bf16 K/V entries widen
+            to it exactly in its normal range): the rotated Q and the
+            unnormalised softmax probabilities entering the P.V product (taken
+            relative to the row maximum rounded up to a whole power of two,
+            see forward_tree).  Pairs of bf16 values
+            (hi + lo, about 16 significant bits): every activation that enters
+            a weight projection - the normalised activations, the attention
+            output and the SwiGLU product.  The residual stream and the logits
+            are never rounded.  Integer decisions (argmax, acceptance) are compared in
             this mode so both sides decide in the same precision.
 
 Pins (tests/test_oracle_*.py): brute-force agreement with an independently
@@ -61,6 +65,18 @@ def bf16_round(x):
     lsb = (b >> np.uint64(16)) & np.uint64(1)
     r = ((b + np.uint64(0x7FFF) + lsb) >> np.uint64(16)) << np.uint64(16)
     return r.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def bf16_split_round(x):
+    """Value carried as a pair of bfloat16 numbers, hi = bf16(x) and lo = bf16(x - hi):
+    returns hi + lo (about 16 significant bits)."""
+    hi = bf16_round(x)
+    return hi + bf16_round(np.asarray(x, dtype=np.float64) - hi)
+
+
+def fp16_round(x):
+    """Round float64 -> float32 -> IEEE half (nearest even), returned as float64."""
+    return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float16).astype(np.float64)
 
 
 def _widen(a):
@@ -186,7 +202,9 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None):
     slot P + r until commit).  Does not modify `kv`."""
     cfg = model.cfg
     rounding = mode == "R" and cfg.dtype == DTYPE_BF16
-    rb = bf16_round if rounding else (lambda a: a)
+    rb = bf16_round if rounding else (lambda a: a)               # single bf16 value
+    rb2 = bf16_split_round if rounding else (lambda a: a)        # hi + lo bf16 pair (projection inputs)
+    rh = fp16_round if rounding else (lambda a: a)               # half precision (attention operands)
     M = len(tok)
     P = kv.P
     Hq, Hkv, hd = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -199,11 +217,11 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None):
     newK = np.zeros((cfg.n_layers, M, Hkv, hd))
     newV = np.zeros((cfg.n_layers, M, Hkv, hd))
     for l in range(L):
-        Xn = rb(rmsnorm(X, model.tensor("norm1", l), cfg.rms_eps))
+        Xn = rb2(rmsnorm(X, model.tensor("norm1", l), cfg.rms_eps))
         Q = (Xn @ model.tensor("wq", l).T).reshape(M, Hq, hd)
         K = (Xn @ model.tensor("wk", l).T).reshape(M, Hkv, hd)
         V = (Xn @ model.tensor("wv", l).T).reshape(M, Hkv, hd)
-        Q = rb(rope(Q, pos, cfg.rope_theta))
+        Q = rh(rope(Q, pos, cfg.rope_theta))
         K = rb(rope(K, pos, cfg.rope_theta))
         V = rb(V)
         newK[l], newV[l] = K, V
@@ -217,28 +235,29 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None):
             s_tree = np.where(vis, s_tree, -np.inf)
             s = np.concatenate([s_ctx, s_tree], axis=1)
             if rounding:
-                # bf16 probabilities: exponentials relative to the row maximum rounded UP to
-                # a whole power of two.  Rounding to bf16 commutes with scaling by powers of
-                # two, so this is independent of the order in which keys are visited.
+                # half-precision probabilities: exponentials relative to the row maximum
+                # rounded UP to a whole power of two.  Rounding commutes with scaling by
+                # powers of two (above the subnormal range), so this is independent of the
+                # order in which keys are visited.
                 t = s * LOG2E
                 m = np.ceil(np.max(t, axis=1, keepdims=True))
-                p = rb(np.exp2(t - m))                              # masked entries -> 0
+                p = rh(np.exp2(t - m))                              # masked entries -> 0
             else:
                 m = np.max(s, axis=1, keepdims=True)
                 p = np.exp(s - m)                                   # masked entries -> 0
             denom = np.sum(p, axis=1, keepdims=True)
             vals = np.concatenate([Vc, V[:, g, :]], axis=0)         # [P+M][hd]
             A[:, h, :] = (p @ vals) / denom
-        A = rb(A.reshape(M, Hq * hd))
+        A = rb2(A.reshape(M, Hq * hd))
         X = X + A @ model.tensor("wo", l).T
 
-        Xn = rb(rmsnorm(X, model.tensor("norm2", l), cfg.rms_eps))
+        Xn = rb2(rmsnorm(X, model.tensor("norm2", l), cfg.rms_eps))
         gate = Xn @ model.tensor("wg", l).T
         up = Xn @ model.tensor("wu", l).T
-        act = rb(silu(gate) * up)
+        act = rb2(silu(gate) * up)
         X = X + act @ model.tensor("wd", l).T
 
-    Xf = rb(rmsnorm(X, model.tensor("norm_f"), cfg.rms_eps))
+    Xf = rb2(rmsnorm(X, model.tensor("norm_f"), cfg.rms_eps))
     logits = Xf @ model.tensor("lm_head").T
     return logits, newK, newV
 

@@ -11,8 +11,12 @@
 // up to 4 query heads of the same KV head, one wave per head, all M rows of that head per
 // wave - so each K/V byte is read from HBM once per KV head.
 //
-// MFMA formulation (v_mfma_f32_16x16x32_bf16), chosen so that no operand needs a transpose
-// or a cross-lane shuffle:
+// The two products run in IEEE half precision (v_mfma_f32_16x16x32_f16): the cache stays bf16
+// and its entries are widened to half while they are staged into LDS (exact in half's normal
+// range), Q arrives in half, and the probabilities are rounded to half - 11 significant bits
+// instead of bf16's 8 where it matters most for the logits.
+//
+// MFMA formulation, chosen so that no operand needs a transpose or a cross-lane shuffle:
 //   S^T[key][query] = K . Q^T     A = K tile from LDS (16 keys x 32 dims per step)
 //                                 B = Q fragments, resident in registers
 //   lane l then holds query (l % 16) and 4 keys of each 16-key tile, so the soft-max
@@ -22,7 +26,7 @@
 //                                 the cache ([head_dim][16 tokens]) exactly for this.
 // Soft-max is the running-max / rescale recurrence in fp32 on scores in log2 units, with the
 // reference rounded up to a whole number so that every rescale is an exact power of two;
-// probabilities 2^(s - ref) are rounded to bf16 for the second product and the row sum
+// probabilities 2^(s - ref) are rounded to half for the second product and the row sum
 // accumulates those rounded values (an extra MFMA against an all-ones operand, fp32 exact).
 // Partial (max, sum, O) per split are combined by k_attn_merge.
 #include <stdlib.h>
@@ -30,7 +34,7 @@
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -40,7 +44,7 @@ namespace {
 constexpr int KB = TS_ATTN_KB;   // keys per block
 
 struct AttnArgs {
-  const bf16_t* Qb;          // [rows][Hq*HD]
+  const bf16_t* Qb;          // [rows][Hq*HD], IEEE half bit patterns
   const uint64_t* row_anc;   // [rows]
   const SeqDesc* seqs;
   float* part_o;             // [splits][R][Hq][HD]
@@ -49,8 +53,13 @@ struct AttnArgs {
   float scale;               // 1/sqrt(head_dim) * log2(e): scores are kept in log2 units
 };
 
+// 8 cache entries bf16 -> half (exact in half's normal range), done while staging into LDS
+__device__ __forceinline__ u32x4 to_half8(u32x4 v) {
+  return u32x4{bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w)};
+}
+
 union Pack8 {
-  bf16x8 v;
+  f16x8 v;
   u32x2 h[2];
   uint32_t u[4];
 };
@@ -98,14 +107,14 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
   const TS_GLOBAL int32_t* ptab = (const TS_GLOBAL int32_t*)sd.page_table;
 
   // resident query fragments and ancestor masks of this wave's head
-  bf16x8 qf[MT][KSQ];
+  f16x8 qf[MT][KSQ];
   uint64_t anc[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int lrow = (tile0 + mt) * 16 + l15;
     const bf16_t* qp = a.Qb + (size_t)(sd.row0 + lrow) * a.Hq * HD + (size_t)h * HD + g4 * 8;
 #pragma unroll
-    for (int ks = 0; ks < KSQ; ++ks) qf[mt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 32);
+    for (int ks = 0; ks < KSQ; ++ks) qf[mt][ks] = *reinterpret_cast<const f16x8*>(qp + ks * 32);
     anc[mt] = lrow < M ? a.row_anc[sd.row0 + lrow] : 0ull;
   }
 
@@ -121,7 +130,7 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
 
   Pack8 ones;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) ones.u[i] = 0x3f803f80u;   // bf16 1.0 x 8
+  for (int i = 0; i < 4; ++i) ones.u[i] = 0x3c003c00u;   // half 1.0 x 8
 
   // Staging of one key block (4 pages).  The page loop is wave-uniform, so each page-table
   // entry is one scalar load and the data loads of all four pages go out back to back.
@@ -153,10 +162,10 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
         if (VPG % NTHR != 0 && w >= VPG) continue;
         if (w < VPP) {
           const int t = w / (HD / 8), dv = w % (HD / 8);
-          *reinterpret_cast<u32x4*>(&ks_[buf][p * 16 + t][dv * 8]) = stage[p * JP + j];
+          *reinterpret_cast<u32x4*>(&ks_[buf][p * 16 + t][dv * 8]) = to_half8(stage[p * JP + j]);
         } else {
           const int w2 = w - VPP;
-          const u32x4 v = stage[p * JP + j];     // 8 tokens; rows are only 8-byte aligned
+          const u32x4 v = to_half8(stage[p * JP + j]);     // 8 tokens; rows are only 8-byte aligned
           *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8]) = u32x2{v.x, v.y};
           *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8 + 4]) = u32x2{v.z, v.w};
         }
@@ -187,10 +196,10 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
         for (int mt = 0; mt < MT; ++mt) s[kt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KSQ; ++ks) {
-          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&ks_[cur][(2 * k2 + kt) * 16 + l15][ks * 32 + g4 * 8]);
+          const f16x8 ka = *reinterpret_cast<const f16x8*>(&ks_[cur][(2 * k2 + kt) * 16 + l15][ks * 32 + g4 * 8]);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
-            s[kt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[mt][ks], s[kt][mt], 0, 0, 0);
+            s[kt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qf[mt][ks], s[kt][mt], 0, 0, 0);
         }
       }
 
@@ -236,7 +245,7 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 4; r += 2)
-            pb[mt].u[kt * 2 + (r >> 1)] = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s[kt][mt][r], a.scale, -m_use)),
+            pb[mt].u[kt * 2 + (r >> 1)] = pack_f16x2(__builtin_amdgcn_exp2f(fmaf(s[kt][mt][r], a.scale, -m_use)),
                                                       __builtin_amdgcn_exp2f(fmaf(s[kt][mt][r + 1], a.scale, -m_use)));
       }
       // the reference moves rarely after the first blocks: skip the O rescale when no row's did
@@ -250,7 +259,7 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
       // ---- O^T += V^T . P^T ; row sums of the rounded probabilities from an all-ones operand ---
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const f32x4 ps = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.v, pb[mt].v, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        const f32x4 ps = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.v, pb[mt].v, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
         l_run[mt] = fmaf(l_run[mt], alpha[mt], ps[0]);
       }
 #pragma unroll
@@ -260,7 +269,7 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
         va.h[1] = *reinterpret_cast<const u32x2*>(&vs_[cur][2 * k2 + 1][dt * 16 + l15][g4 * 4]);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          o[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va.v, pb[mt].v, o[dt][mt], 0, 0, 0);
+          o[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb[mt].v, o[dt][mt], 0, 0, 0);
       }
     }
 
@@ -288,7 +297,7 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
 
 // Combine the splits: out = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s, stored as bf16.
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                    bf16_t* __restrict__ Ab, int R, int Hq, int HD, int splits) {
+                                                    bf16_t* __restrict__ Ab, size_t lo_plane, int R, int Hq, int HD, int splits) {
   // one (row, head) pair per group of HD/4 threads, 16-byte accesses
   const int tpp = HD / 4;
   const size_t n_slots = (size_t)R * Hq;
@@ -318,10 +327,16 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ pa
       num.x += w * o8[u].x; num.y += w * o8[u].y; num.z += w * o8[u].z; num.w += w * o8[u].w;
     }
   }
-  uint2 out;
-  out.x = pack_bf16x2(num.x / den, num.y / den);
-  out.y = pack_bf16x2(num.z / den, num.w / den);
-  *reinterpret_cast<uint2*>(Ab + slot * HD + d4 * 4) = out;
+  // the attention output feeds the O projection: (hi, lo) bf16 planes
+  const float o4[4] = {num.x / den, num.y / den, num.z / den, num.w / den};
+  bf16_t hi[4], lo[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split_bf16(o4[i], hi[i], lo[i]);
+  uint2 oh, ol;
+  oh.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); oh.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
+  ol.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); ol.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
+  *reinterpret_cast<uint2*>(Ab + slot * HD + d4 * 4) = oh;
+  *reinterpret_cast<uint2*>(Ab + lo_plane + slot * HD + d4 * 4) = ol;
 }
 
 // Rows are covered by RS waves per head, MT tiles of 16 rows each: (tiles -> RS x MT)
@@ -396,5 +411,5 @@ void launch_attn_merge(ts_model* m, int R, int splits) {
   const ts_model_config& c = m->cfg;
   const int per_block = 256 / (c.head_dim / 4);
   hipLaunchKernelGGL(k_attn_merge, dim3((R * c.n_q_heads + per_block - 1) / per_block), dim3(256), 0, m->stream, m->attn_part_o, m->attn_part_ml,
-                     (bf16_t*)m->Ab, R, c.n_q_heads, c.head_dim, splits);
+                     (bf16_t*)m->Ab, act_plane(m, m->q_dim), R, c.n_q_heads, c.head_dim, splits);
 }

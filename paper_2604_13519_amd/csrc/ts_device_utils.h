@@ -28,6 +28,26 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, ts_bf16x2));
 }
 
+// value -> (hi, lo) bf16 pair with hi = bf16(x), lo = bf16(x - hi): about 16 significant bits
+__device__ __forceinline__ void split_bf16(float x, bf16_t& hi, bf16_t& lo) {
+  hi = f32_to_bf16(x);
+  lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
+
+// two floats -> packed IEEE half pair (low half = a), round to nearest even
+typedef _Float16 ts_f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_f16x2(float a, float b) {
+  const ts_f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, ts_f16x2));
+}
+// packed bf16 pair -> packed half pair (exact in the normal range of half)
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
+  return pack_f16x2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+}
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
+  return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
 __device__ __forceinline__ float ld_f32(const float* p) { return *p; }
 __device__ __forceinline__ float ld_f32(const bf16_t* p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void st_from_f32(float* p, float v) { *p = v; }

@@ -9,7 +9,10 @@
 //    the weights of the next PF chunks are in flight (register ring) while the current one
 //    is multiplied.
 //  * The activations X (R x K, tiny) are shared by the WAVES waves of a workgroup through a
-//    double-buffered LDS chunk and read as A operands with 16-byte LDS loads.
+//    double-buffered LDS chunk and read as A operands with 16-byte LDS loads.  Each activation
+//    is a (hi, lo) pair of bf16 values (about 16 significant bits): two MFMAs per weight
+//    fragment.  The matrix cores idle most of the time in a weight-streaming kernel, so the
+//    extra precision costs no bandwidth.
 //  * K is split across workgroups (grid.y) so that every CU streams; partial sums go to a
 //    fp32 [split][row][col] buffer that the next row-wise kernel adds up in a fixed order
 //    (deterministic, no atomics).
@@ -26,7 +29,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 struct GemmArgs {
-  const bf16_t* X;     // [rows][K] row-major, rows padded to a multiple of 16 in memory
+  const bf16_t* X;     // [2][rows][K]: hi plane, then lo plane (x = hi + lo), rows padded in memory
+  size_t x_plane;      // elements between the planes
   const bf16_t* Wt;    // tiled weights
   float* out;          // [split][R][N] partial sums (nullptr for ARGMAX)
   float* logits;       // [R][N] or nullptr (ARGMAX only)
@@ -46,9 +50,10 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
   constexpr int XS = KC + 8;                // LDS row stride in elements (+16 B: bank spread, keeps alignment)
   constexpr int NTHR = 64 * WAVES;
   constexpr int NBUF = PF + 1;              // weight register ring
-  constexpr int XV = MT * 16 * KC / 8;      // 16-byte vectors per X chunk
+  constexpr int XV1 = MT * 16 * KC / 8;     // 16-byte vectors per X chunk and plane
+  constexpr int XV = 2 * XV1;               // both planes
   constexpr int XPT = (XV + NTHR - 1) / NTHR;
-  __shared__ __attribute__((aligned(16))) bf16_t xs[2][MT * 16][XS];
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][2][MT * 16][XS];   // [buffer][plane][row][k]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, g = lane >> 4;
@@ -88,8 +93,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
       if (XV % NTHR == 0 || v < XV) {
-        const int row = v / (KC / 8), cv = v % (KC / 8);
-        xr[p] = *reinterpret_cast<const u32x4*>(a.X + (size_t)(row0 + row) * a.K + kb + cv * 8);
+        const int pl = v / XV1, u = v % XV1;
+        const int row = u / (KC / 8), cv = u % (KC / 8);
+        xr[p] = *reinterpret_cast<const u32x4*>(a.X + pl * a.x_plane + (size_t)(row0 + row) * a.K + kb + cv * 8);
       }
     }
   };
@@ -98,22 +104,30 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
       if (XV % NTHR == 0 || v < XV) {
-        const int row = v / (KC / 8), cv = v % (KC / 8);
-        *reinterpret_cast<u32x4*>(&xs[buf][row][cv * 8]) = xr[p];
+        const int pl = v / XV1, u = v % XV1;
+        const int row = u / (KC / 8), cv = u % (KC / 8);
+        *reinterpret_cast<u32x4*>(&xs[buf][pl][row][cv * 8]) = xr[p];
       }
     }
   };
+  // activations are (hi, lo) bf16 pairs: both planes multiply the same weight fragment and
+  // add into the same fp32 accumulator
   auto mma_chunk = [&](const bf16x8 (&wc)[NT][KSTEPS], int buf) {
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
-      bf16x8 af[MT];
+      bf16x8 ah[MT], al[MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][mt * 16 + l15][ks * 32 + g * 8]);
+      for (int mt = 0; mt < MT; ++mt) {
+        ah[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][0][mt * 16 + l15][ks * 32 + g * 8]);
+        al[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][1][mt * 16 + l15][ks * 32 + g * 8]);
+      }
 #pragma unroll
       for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
+          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
+        }
     }
   };
 
@@ -205,19 +219,20 @@ void launch_mt(int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
   }
 }
 
-// The compiled tile shapes.  shape id -> (NT, WAVES, KC, PF).
+// The compiled tile shapes.  shape id -> (NT, WAVES, KC, PF).  The LDS holds two buffers of
+// two planes of the activation chunk, which keeps KC at 128 for 80 rows.
 constexpr int kNumShapes = 4;
 const int kShapeNT[kNumShapes] = {1, 2, 1, 2};
 const int kShapeWaves[kNumShapes] = {4, 4, 8, 8};
-const int kShapeKC[kNumShapes] = {128, 128, 256, 256};
+const int kShapeKC[kNumShapes] = {128, 128, 128, 128};
 
 template <bool ARGMAX>
 void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
   switch (shape) {
     case 0: launch_mt<1, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
     case 1: launch_mt<2, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
-    case 2: launch_mt<1, 8, 256, 1, ARGMAX>(mt, grid, s, a); break;
-    default: launch_mt<2, 8, 256, 1, ARGMAX>(mt, grid, s, a); break;
+    case 2: launch_mt<1, 8, 128, 2, ARGMAX>(mt, grid, s, a); break;
+    default: launch_mt<2, 8, 128, 2, ARGMAX>(mt, grid, s, a); break;
   }
 }
 
@@ -256,6 +271,7 @@ GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K, bool allow_split) {
 void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, GemmPlan plan,
                       bool argmax, float* logits) {
   GemmArgs a;
+  a.x_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * K;
   a.X = X; a.Wt = Wt; a.out = out; a.logits = logits;
   a.aval = m->amax_val; a.aidx = m->amax_idx;
   a.R = R; a.N = N; a.K = K;

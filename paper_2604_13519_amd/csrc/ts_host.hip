@@ -141,10 +141,11 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs) {
     const int scap = std::max(seqs, 1);
     const size_t esz = m->esz;
     if ((st = dev_alloc_bytes((void**)&m->H, (size_t)alloc_rows * c.d_model * 4, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Xn, (size_t)alloc_rows * c.d_model * esz, true))) return st;
+    const size_t planes = c.dtype == TS_DTYPE_BF16 ? 2 : 1;     // bf16 projection inputs are (hi, lo) pairs
+    if ((st = dev_alloc_bytes(&m->Xn, planes * alloc_rows * c.d_model * esz, true))) return st;
     if ((st = dev_alloc_bytes(&m->Qb, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Ab, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Fb, (size_t)alloc_rows * c.d_ffn * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Ab, planes * alloc_rows * m->q_dim * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Fb, planes * alloc_rows * c.d_ffn * esz, true))) return st;
     size_t pe = 0;
     if (c.dtype == TS_DTYPE_BF16) {
       const int Ns[4] = {m->qkv_dim, c.d_model, 2 * c.d_ffn, c.d_model};

@@ -85,10 +85,10 @@ struct ts_model {
   // workspace, sized for ws_rows rows (multiple of TS_MROWS_PER_BLOCK)
   int ws_rows, ws_seqs;
   float* H;                     // residual stream [rows][d] fp32
-  void* Xn;                     // normalised activations [rows][d]           (storage dtype)
-  void* Qb;                     // rotated queries [rows][q_dim]               (storage dtype)
-  void* Ab;                     // attention output [rows][q_dim]              (storage dtype)
-  void* Fb;                     // SwiGLU product [rows][F]                    (storage dtype)
+  void* Xn;                     // normalised activations [rows][d]; bf16 models: [2][rows][d] hi/lo planes
+  void* Qb;                     // rotated queries [rows][q_dim]; float, or IEEE half for bf16 models
+  void* Ab;                     // attention output [rows][q_dim]; bf16 models: hi/lo planes
+  void* Fb;                     // SwiGLU product [rows][F]; bf16 models: hi/lo planes
   float* part;                  // split-K partial sums, [S][rows][N] fp32
   size_t part_elems;
   float* attn_part_o;           // [splits][rows][Hq][hd]
@@ -136,6 +136,9 @@ void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out
 int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs);
 void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int layer, int splits, int max_M);
 void launch_attn_merge(ts_model* m, int R, int splits);
+
+// element offset between the hi and lo planes of a projection input with K columns
+inline size_t act_plane(const ts_model* m, int K) { return (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * K; }
 
 // profiling bracket
 void prof_begin(ts_model* m, const char* name);

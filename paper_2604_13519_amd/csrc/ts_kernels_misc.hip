@@ -7,6 +7,15 @@
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 
+// rotated queries: float, or IEEE half bits for bf16 models (the attention products run in
+// half precision; bf16 K/V entries widen to half exactly)
+__device__ __forceinline__ void st_q(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_q(bf16_t* p, float v) { *p = f32_to_f16_bits(v); }
+
+// store an activation that feeds a projection: float as is, bf16 as a (hi, lo) pair of planes
+__device__ __forceinline__ void st_act(float* p, size_t, float v) { *p = v; }
+__device__ __forceinline__ void st_act(bf16_t* p, size_t lo_plane, float v) { split_bf16(v, p[0], p[lo_plane]); }
+
 // ---------------------------------------------------------------------------------
 // weight re-tiling (model load): row-major [N][K] bf16 -> MFMA operand tiles.
 // Tile (nt, kt) covers out-features [16 nt, 16 nt + 16) x in-features [32 kt, 32 kt + 32)
@@ -80,13 +89,14 @@ void launch_rope_table(ts_model* m, const RowMeta& rm, int R) {
 
 // ---------------------------------------------------------------------------------
 // residual update + RMSNorm:  H[r] += sum_s part[s][r]  (skipped when n_parts = 0),
-// Xn[r] = T( H[r] * rsqrt(mean(H[r]^2) + eps) * gain ).
+// Xn[r] = H[r] * rsqrt(mean(H[r]^2) + eps) * gain, stored as float (fp32 models) or as a
+// (hi, lo) pair of bf16 planes (bf16 models: every projection input is such a pair).
 // One block of 1024 threads per row, 16-byte accesses; needs d_model % 4 == 0.
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const float* __restrict__ part, int n_parts,
                                                size_t part_stride, const float* __restrict__ gain,
-                                               T* __restrict__ Xn, int d, float eps) {
+                                               T* __restrict__ Xn, size_t lo_plane, int d, float eps) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   float4* h4 = reinterpret_cast<float4*>(H + (size_t)r * d);
@@ -121,10 +131,10 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
   for (int i = threadIdx.x; i < d4; i += 1024) {
     const float4 v = h4[i], g = g4[i];
     T* o = Xn + (size_t)r * d + 4 * i;
-    st_from_f32(o + 0, v.x * inv * g.x);
-    st_from_f32(o + 1, v.y * inv * g.y);
-    st_from_f32(o + 2, v.z * inv * g.z);
-    st_from_f32(o + 3, v.w * inv * g.w);
+    st_act(o + 0, lo_plane, v.x * inv * g.x);
+    st_act(o + 1, lo_plane, v.y * inv * g.y);
+    st_act(o + 2, lo_plane, v.z * inv * g.z);
+    st_act(o + 3, lo_plane, v.w * inv * g.w);
   }
 }
 
@@ -132,10 +142,10 @@ void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part
   ProfScope ps(m, "residual_rmsnorm");
   if (m->cfg.dtype == TS_DTYPE_BF16)
     hipLaunchKernelGGL(k_norm<bf16_t>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (bf16_t*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
+                       (bf16_t*)m->Xn, act_plane(m, m->cfg.d_model), m->cfg.d_model, m->cfg.rms_eps);
   else
     hipLaunchKernelGGL(k_norm<float>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (float*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
+                       (float*)m->Xn, (size_t)0, m->cfg.d_model, m->cfg.rms_eps);
 }
 
 // ---------------------------------------------------------------------------------
@@ -170,8 +180,8 @@ __global__ __launch_bounds__(64) void k_rope_kv(const float* __restrict__ part, 
   }
   if (head < Hq) {
     const float2 w = cs[(size_t)r * half + j];
-    st_from_f32(Qb + (size_t)r * q_dim + c1, x1 * w.x - x2 * w.y);
-    st_from_f32(Qb + (size_t)r * q_dim + c2, x2 * w.x + x1 * w.y);
+    st_q(Qb + (size_t)r * q_dim + c1, x1 * w.x - x2 * w.y);
+    st_q(Qb + (size_t)r * q_dim + c2, x2 * w.x + x1 * w.y);
     return;
   }
   const SeqDesc sd = seqs[row_seq[r]];
@@ -209,8 +219,8 @@ void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_part
 // fused projection whose 16-column tiles alternate gate, up, gate, up, ...
 // ---------------------------------------------------------------------------------
 template <typename T>
-__global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t part_stride, T* __restrict__ Fb, int R,
-                         int F) {
+__global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t part_stride, T* __restrict__ Fb,
+                         size_t lo_plane, int R, int F) {
   const size_t total = (size_t)R * F;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int r = (int)(i / F), f = (int)(i % F);
@@ -221,7 +231,7 @@ __global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t par
       g += p[(size_t)s * part_stride];
       u += p[(size_t)s * part_stride + 16];
     }
-    st_from_f32(Fb + i, g / (1.0f + expf(-g)) * u);
+    st_act(Fb + i, lo_plane, g / (1.0f + expf(-g)) * u);
   }
 }
 
@@ -232,9 +242,9 @@ void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride) {
   int blocks = (int)((total + 255) / 256);
   if (blocks > 4096) blocks = 4096;
   if (m->cfg.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_swiglu<bf16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (bf16_t*)m->Fb, R, F);
+    hipLaunchKernelGGL(k_swiglu<bf16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (bf16_t*)m->Fb, act_plane(m, F), R, F);
   else
-    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, R, F);
+    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, (size_t)0, R, F);
 }
 
 // ---------------------------------------------------------------------------------
