@@ -70,9 +70,12 @@ enum { TS_MAX_NODES = 64, TS_PAGE_SIZE = 16 };
 /* Decoder shape: pre-norm blocks with RMSNorm, rotary embedding (pair (j, j+hd/2)
  * rotated by pos * rope_theta^(-2j/hd)), grouped-query attention with softmax scale
  * 1/sqrt(head_dim), SwiGLU feed-forward, no biases, untied embedding / lm_head.
- * dtype is the storage type of weights and KV cache; TS_DTYPE_BF16 computes with
- * bf16 MFMA and fp32 accumulation and needs d_model, n_q_heads*head_dim and d_ffn
- * to be multiples of 128, head_dim 64 or 128; TS_DTYPE_F32 computes in fp32. */
+ * dtype is the storage type of weights and KV cache.  TS_DTYPE_BF16 computes the
+ * projections with bf16 MFMA and fp32 accumulation (activations enter as hi+lo
+ * pairs of bf16 values), the attention products in IEEE half with fp32 soft-max,
+ * keeps the residual stream and logits in fp32, and needs d_model,
+ * n_q_heads*head_dim and d_ffn to be multiples of 128 and head_dim 64 or 128.
+ * TS_DTYPE_F32 computes in fp32. */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rope_theta, rms_eps;
@@ -175,6 +178,9 @@ ts_status ts_kv_commit(ts_kv* kv);
  * It returns the number of kinds through n_entries. */
 typedef struct { const char* name; int32_t launches; float total_ms; } ts_profile_entry;
 ts_status ts_profile_enable(ts_model* m, int32_t enable);
+/* Restrict the bracketing to launches of one kernel kind (e.g. "gemm_gate_up"), so that
+ * its timing is not disturbed by events around every other launch; NULL = all kinds. */
+ts_status ts_profile_filter(ts_model* m, const char* kind_or_null);
 ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_entries, int32_t* n_entries);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ TS_MAX_NODES, TS_PAGE_SIZE = 64, 16
 EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits",
            "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export",
            "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_verify", "ts_verify_batch",
-           "ts_kv_commit", "ts_profile_enable", "ts_profile_read")
+           "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read")
 
 
 class TsError(RuntimeError):
@@ -82,6 +82,7 @@ def load_library(path=None):
         "ts_verify_batch": [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, i32p, i32p, i32p, i32p, i32p, i32p, i32p],
         "ts_kv_commit": [C.c_void_p],
         "ts_profile_enable": [C.c_void_p, C.c_int32],
+        "ts_profile_filter": [C.c_void_p, C.c_char_p],
         "ts_profile_read": [C.c_void_p, C.POINTER(ts_profile_entry), C.c_int32, i32p],
     }
     for name, args in sigs.items():
@@ -246,6 +247,10 @@ def ts_kv_commit(kv):
 
 def ts_profile_enable(model, enable):
     _check(load_library().ts_profile_enable(model, int(bool(enable))))
+
+
+def ts_profile_filter(model, kind=None):
+    _check(load_library().ts_profile_filter(model, kind.encode() if kind else None))
 
 
 def ts_profile_read(model, max_entries=64):

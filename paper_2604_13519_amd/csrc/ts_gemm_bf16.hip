@@ -44,10 +44,10 @@ struct GemmArgs {
   int amax_parts;
 };
 
-template <int MT, int NT, int WAVES, int KC, int PF, bool ARGMAX>
+template <int MT, int NT, int WAVES, int KC, int PF, bool ARGMAX, int XPAD = 8>
 __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
   constexpr int KSTEPS = KC / 32;           // MFMA k-steps per chunk
-  constexpr int XS = KC + 8;                // LDS row stride in elements (+16 B: bank spread, keeps alignment)
+  constexpr int XS = KC + XPAD;             // LDS row stride in elements (+16 B: bank spread, keeps alignment)
   constexpr int NTHR = 64 * WAVES;
   constexpr int NBUF = PF + 1;              // weight register ring
   constexpr int XV1 = MT * 16 * KC / 8;     // 16-byte vectors per X chunk and plane
@@ -131,11 +131,14 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
     }
   };
 
-  // prologue: first PF weight chunks in flight, first X chunk staged
+  // Vector-memory loads complete in issue order as far as the wait counter is concerned, so
+  // the small X loads are always issued BEFORE the weight prefetch of the same step: waiting
+  // for X then leaves the newest weight chunks in flight.
+  load_x(0);
+  __builtin_amdgcn_sched_barrier(0);        // keep the issue order
 #pragma unroll
   for (int b = 0; b < PF; ++b)
     if (b < n_chunks) load_w(w[b], b);
-  load_x(0);
   store_x(0);
   __syncthreads();
 
@@ -145,9 +148,11 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
     for (int b = 0; b < NBUF; ++b) {
       const int c = c0 + b;
       if (c < n_chunks) {
-        if (c + PF < n_chunks) load_w(w[(b + PF) % NBUF], c + PF);
         const bool more = c + 1 < n_chunks;
         if (more) load_x(c + 1);
+        __builtin_amdgcn_sched_barrier(0);  // X loads first, then the weight prefetch
+        if (c + PF < n_chunks) load_w(w[(b + PF) % NBUF], c + PF);
+        __builtin_amdgcn_sched_barrier(0);
         mma_chunk(w[b], c & 1);
         if (more) store_x((c + 1) & 1);
         __syncthreads();
@@ -231,8 +236,8 @@ void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a
   switch (shape) {
     case 0: launch_mt<1, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
     case 1: launch_mt<2, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
-    case 2: launch_mt<1, 8, 128, 2, ARGMAX>(mt, grid, s, a); break;
-    default: launch_mt<2, 8, 128, 2, ARGMAX>(mt, grid, s, a); break;
+    case 2: launch_mt<1, 8, 128, 1, ARGMAX>(mt, grid, s, a); break;
+    default: launch_mt<2, 8, 128, 1, ARGMAX>(mt, grid, s, a); break;
   }
 }
 

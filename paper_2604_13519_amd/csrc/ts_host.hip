@@ -730,6 +730,12 @@ extern "C" ts_status ts_profile_enable(ts_model* m, int32_t enable) {
   return TS_OK;
 }
 
+extern "C" ts_status ts_profile_filter(ts_model* m, const char* kind) {
+  if (!m) return ts_fail(TS_ERR_INVALID_ARG, "null model");
+  m->prof_filter = kind ? kind : "";
+  return TS_OK;
+}
+
 extern "C" ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_entries, int32_t* n_entries) {
   if (!m || !n_entries || (max_entries > 0 && !entries)) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
   (void)hipSetDevice(m->device);

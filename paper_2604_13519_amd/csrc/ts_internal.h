@@ -103,6 +103,7 @@ struct ts_model {
   int32_t* res_host;            // pinned, ws_seqs * TS_RESULT_INTS
   // profiling
   bool prof_on;
+  std::string prof_filter;      // empty = bracket every kernel kind
   std::vector<ProfRec> prof;
   std::vector<hipEvent_t> ev_pool; size_t ev_used;
   int last_rows;
@@ -145,6 +146,10 @@ void prof_begin(ts_model* m, const char* name);
 void prof_end(ts_model* m);
 struct ProfScope {
   ts_model* m;
-  ProfScope(ts_model* mm, const char* name) : m(mm) { if (m->prof_on) prof_begin(m, name); }
-  ~ProfScope() { if (m->prof_on) prof_end(m); }
+  bool on;
+  ProfScope(ts_model* mm, const char* name) : m(mm) {
+    on = m->prof_on && (m->prof_filter.empty() || m->prof_filter == name);
+    if (on) prof_begin(m, name);
+  }
+  ~ProfScope() { if (on) prof_end(m); }
 };
