@@ -13,9 +13,16 @@
 //    is a (hi, lo) pair of bf16 values (about 16 significant bits): two MFMAs per weight
 //    fragment.  The matrix cores idle most of the time in a weight-streaming kernel, so the
 //    extra precision costs no bandwidth.
-//  * K is split across workgroups (grid.y) so that every CU streams; partial sums go to a
-//    fp32 [split][row][col] buffer that the next row-wise kernel adds up in a fixed order
-//    (deterministic, no atomics).
+//  * K is split two ways.  Inside a workgroup, KW waves share the same output columns and take
+//    alternate k-steps of every chunk; their accumulators are added through LDS in a fixed
+//    order at the end.  Across workgroups (grid.y), partial sums go to a fp32
+//    [split][row][col] buffer that the next row-wise kernel adds up in a fixed order
+//    (deterministic, no atomics).  The in-workgroup split costs no memory traffic, the
+//    cross-workgroup one costs a write and a read of the partial sums, so the planner uses as
+//    little of the second as still fills the chip.
+//  * gate/up variant (SWIGLU): the weight tiles of gate and up alternate, so a wave that owns
+//    two neighbouring tiles holds gate and up of the same 16 features; with no cross-workgroup
+//    split the epilogue applies SiLU(gate) * up and stores the (hi, lo) planes directly.
 //  * lm_head variant (ARGMAX): no split; the epilogue reduces each row's maximum over the
 //    workgroup's columns and emits one (value, index) partial per row, so the full logits
 //    never have to reach memory.
@@ -36,6 +43,8 @@ struct GemmArgs {
   float* logits;       // [R][N] or nullptr (ARGMAX only)
   float* aval;         // [R][amax_parts]
   int32_t* aidx;
+  bf16_t* act_out;     // SWIGLU: [2][rows][N/2] hi/lo planes of the gated product
+  size_t act_plane;
   int R, N, K;
   int kper;            // k elements per split
   int n_tiles;         // ceil(N / 16)
@@ -44,30 +53,56 @@ struct GemmArgs {
   int amax_parts;
 };
 
-template <int MT, int NT, int WAVES, int KC, int PF, bool ARGMAX, int XPAD = 8>
-__global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
+enum { MODE_PARTIAL = 0, MODE_ARGMAX = 1, MODE_SWIGLU = 2 };
+
+template <int MT, int NT, int CS, int KW, int KC, int PF, int MODE, int XPAD = 8>
+__global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
+  constexpr int WAVES = CS * KW;            // CS column sets x KW k-step owners
+  constexpr bool ARGMAX = MODE == MODE_ARGMAX;
   constexpr int KSTEPS = KC / 32;           // MFMA k-steps per chunk
+  constexpr int KSW = KSTEPS / KW;          // ... of which this wave multiplies KSW
+  static_assert(KSTEPS % KW == 0 && KSW >= 1, "k-steps of a chunk must divide among the k-waves");
+  static_assert(!(ARGMAX && KW != 1), "the arg-max epilogue expects one wave per column set");
+  static_assert(MODE != MODE_SWIGLU || NT == 2, "gate and up tiles alternate");
   constexpr int XS = KC + XPAD;             // LDS row stride in elements (+16 B: bank spread, keeps alignment)
   constexpr int NTHR = 64 * WAVES;
   constexpr int NBUF = PF + 1;              // weight register ring
   constexpr int XV1 = MT * 16 * KC / 8;     // 16-byte vectors per X chunk and plane
   constexpr int XV = 2 * XV1;               // both planes
   constexpr int XPT = (XV + NTHR - 1) / NTHR;
-  __shared__ __attribute__((aligned(16))) bf16_t xs[2][2][MT * 16][XS];   // [buffer][plane][row][k]
+  // activation chunks [buffer][plane][row][k]; the same memory later serves the k-wave reduction
+  constexpr size_t XS_BYTES = sizeof(bf16_t) * 2 * 2 * MT * 16 * XS;
+  constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * MT * 4 * NT * 64 : 0;
+  __shared__ __attribute__((aligned(16))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
+  bf16_t (*xs)[2][MT * 16][XS] = reinterpret_cast<bf16_t (*)[2][MT * 16][XS]>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, g = lane >> 4;
+  const int cs = wave / KW, kq = wave % KW;
   const int row0 = blockIdx.z * TS_MROWS_PER_BLOCK;
   const int kbase0 = blockIdx.y * a.kper;
   const int n_chunks = a.kper / KC;
 
-  const bf16_t* wp[NT];                     // this lane's pointer into each owned tile row
+  // Addresses are (uniform 64-bit base) + (32-bit per-lane byte offset that never changes):
+  // the loads then need no vector address arithmetic inside the loop.
+  const int cs_u = __builtin_amdgcn_readfirstlane(cs), kq_u = __builtin_amdgcn_readfirstlane(kq);
+  const char* wbase[NT];                    // start of this wave's k range in each owned tile row
   int nt_idx[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    nt_idx[t] = (blockIdx.x * WAVES + wave) * NT + t;
+    nt_idx[t] = (blockIdx.x * CS + cs_u) * NT + t;
     const int c = nt_idx[t] < a.n_tiles ? nt_idx[t] : a.n_tiles - 1;   // idle waves re-read a valid tile
-    wp[t] = a.Wt + (((size_t)c * a.kt_count + kbase0 / 32) * 64 + lane) * 8;
+    wbase[t] = reinterpret_cast<const char*>(a.Wt) + ((size_t)c * a.kt_count + kbase0 / 32 + kq_u * KSW) * 1024;
+  }
+  const uint32_t w_lane = lane * 16;
+  const char* xbase = reinterpret_cast<const char*>(a.X) + ((size_t)row0 * a.K + kbase0) * 2;
+  uint32_t x_off[XPT];                      // byte offset of each staged vector within a chunk
+#pragma unroll
+  for (int p = 0; p < XPT; ++p) {
+    const int v = min(tid + p * NTHR, XV - 1);
+    const int pl = v / XV1, u = v % XV1;
+    const int row = u / (KC / 8), cv = u % (KC / 8);
+    x_off[p] = (uint32_t)((pl * a.x_plane + (size_t)row * a.K + cv * 8) * 2);
   }
 
   f32x4 acc[MT][NT];
@@ -76,28 +111,22 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 w[NBUF][NT][KSTEPS];
+  bf16x8 w[NBUF][NT][KSW];
   u32x4 xr[XPT];
 
-  auto load_w = [&](bf16x8 (&dst)[NT][KSTEPS], int chunk) {
+  auto load_w = [&](bf16x8 (&dst)[NT][KSW], int chunk) {
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-      for (int j = 0; j < KSTEPS; ++j)
+      for (int j = 0; j < KSW; ++j)
         dst[t][j] = __builtin_nontemporal_load(
-            reinterpret_cast<const bf16x8*>(wp[t] + ((size_t)chunk * KSTEPS + j) * 512));
+            reinterpret_cast<const bf16x8*>(wbase[t] + (size_t)chunk * (KSTEPS * 1024) + w_lane + j * 1024));
   };
   auto load_x = [&](int chunk) {
-    const int kb = kbase0 + chunk * KC;
+    const char* xb = xbase + (size_t)chunk * (KC * 2);
 #pragma unroll
-    for (int p = 0; p < XPT; ++p) {
-      const int v = tid + p * NTHR;
-      if (XV % NTHR == 0 || v < XV) {
-        const int pl = v / XV1, u = v % XV1;
-        const int row = u / (KC / 8), cv = u % (KC / 8);
-        xr[p] = *reinterpret_cast<const u32x4*>(a.X + pl * a.x_plane + (size_t)(row0 + row) * a.K + kb + cv * 8);
-      }
-    }
+    for (int p = 0; p < XPT; ++p)
+      if (XV % NTHR == 0 || tid + p * NTHR < XV) xr[p] = *reinterpret_cast<const u32x4*>(xb + x_off[p]);
   };
   auto store_x = [&](int buf) {
 #pragma unroll
@@ -112,14 +141,14 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
   };
   // activations are (hi, lo) bf16 pairs: both planes multiply the same weight fragment and
   // add into the same fp32 accumulator
-  auto mma_chunk = [&](const bf16x8 (&wc)[NT][KSTEPS], int buf) {
+  auto mma_chunk = [&](const bf16x8 (&wc)[NT][KSW], int buf) {
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
+    for (int ks = 0; ks < KSW; ++ks) {
       bf16x8 ah[MT], al[MT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        ah[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][0][mt * 16 + l15][ks * 32 + g * 8]);
-        al[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][1][mt * 16 + l15][ks * 32 + g * 8]);
+        ah[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][0][mt * 16 + l15][(kq * KSW + ks) * 32 + g * 8]);
+        al[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][1][mt * 16 + l15][(kq * KSW + ks) * 32 + g * 8]);
       }
 #pragma unroll
       for (int t = 0; t < NT; ++t)
@@ -131,11 +160,26 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
     }
   };
 
-  // Vector-memory loads complete in issue order as far as the wait counter is concerned, so
-  // the small X loads are always issued BEFORE the weight prefetch of the same step: waiting
-  // for X then leaves the newest weight chunks in flight.
+  // Vector-memory loads complete in issue order as far as the wait counter is concerned, and
+  // the compiler's wait for a load counts every later load that MIGHT not have been issued as
+  // not issued.  Two consequences shape this loop: the small X loads are issued BEFORE the
+  // weight prefetch of the same step (waiting for X then leaves the newest weights in flight),
+  // and the steady-state trips issue both unconditionally - a prefetch under an `if` would
+  // turn every wait for X into a wait for all weights as well.  The last chunks, where
+  // there is nothing left to prefetch, run in a predicated tail.
+  auto step = [&](bf16x8 (&wcur)[NT][KSW], bf16x8 (&wnext)[NT][KSW], int c, bool steady) {
+    const bool more = steady || c + 1 < n_chunks;
+    if (more) load_x(c + 1);
+    __builtin_amdgcn_sched_barrier(0);      // X loads first, then the weight prefetch
+    if (steady || c + PF < n_chunks) load_w(wnext, c + PF);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_chunk(wcur, c & 1);
+    if (more) store_x((c + 1) & 1);
+    __syncthreads();
+  };
+
   load_x(0);
-  __builtin_amdgcn_sched_barrier(0);        // keep the issue order
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int b = 0; b < PF; ++b)
     if (b < n_chunks) load_w(w[b], b);
@@ -143,36 +187,72 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
   __syncthreads();
 
   // NBUF chunks per trip so that ring slots are compile-time register names
-  for (int c0 = 0; c0 < n_chunks; c0 += NBUF) {
+  int c0 = 0;
+  for (; c0 + NBUF + PF <= n_chunks; c0 += NBUF) {
 #pragma unroll
-    for (int b = 0; b < NBUF; ++b) {
-      const int c = c0 + b;
-      if (c < n_chunks) {
-        const bool more = c + 1 < n_chunks;
-        if (more) load_x(c + 1);
-        __builtin_amdgcn_sched_barrier(0);  // X loads first, then the weight prefetch
-        if (c + PF < n_chunks) load_w(w[(b + PF) % NBUF], c + PF);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_chunk(w[b], c & 1);
-        if (more) store_x((c + 1) & 1);
-        __syncthreads();
-      }
-    }
+    for (int b = 0; b < NBUF; ++b) step(w[b], w[(b + PF) % NBUF], c0 + b, true);
+  }
+  for (; c0 < n_chunks; c0 += NBUF) {
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b)
+      if (c0 + b < n_chunks) step(w[b], w[(b + PF) % NBUF], c0 + b, false);
   }
 
   if (!ARGMAX) {
-    float* o = a.out + (size_t)blockIdx.y * a.split_stride;
+    // value of output (row tile mt, row r of the lane group, tile t) goes to memory
+    auto emit = [&](int mt, int r, const float (&v)[NT]) {
+      const int row = row0 + mt * 16 + g * 4 + r;
+      if (row >= a.R) return;
+      if (MODE == MODE_SWIGLU) {
+        const int f = (nt_idx[0] >> 1) * 16 + l15;           // tiles 2j / 2j+1 = gate / up of features 16j..
+        if (nt_idx[1] < a.n_tiles) {
+          const float gv = v[0], uv = v[NT - 1];
+          bf16_t hi, lo;
+          split_bf16(gv / (1.0f + expf(-gv)) * uv, hi, lo);
+          a.act_out[(size_t)row * (a.N / 2) + f] = hi;
+          a.act_out[a.act_plane + (size_t)row * (a.N / 2) + f] = lo;
+        }
+      } else {
+        float* o = a.out + (size_t)blockIdx.y * a.split_stride;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int col = nt_idx[t] * 16 + l15;
-      if (nt_idx[t] < a.n_tiles && col < a.N) {
+        for (int t = 0; t < NT; ++t) {
+          const int col = nt_idx[t] * 16 + l15;
+          if (nt_idx[t] < a.n_tiles && col < a.N) o[(size_t)row * a.N + col] = v[t];
+        }
+      }
+    };
+    if (KW == 1) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int row = row0 + mt * 16 + g * 4 + r;
-            if (row < a.R) o[(size_t)row * a.N + col] = acc[mt][t][r];
-          }
+        for (int r = 0; r < 4; ++r) {
+          float v[NT];
+#pragma unroll
+          for (int t = 0; t < NT; ++t) v[t] = acc[mt][t][r];
+          emit(mt, r, v);
+        }
+    } else {
+      // add the KW accumulators of a column set through LDS (the activation buffers are free
+      // after the loop's last barrier), always in the order kq = 0, 1, ...
+      constexpr int SLOTS = MT * 4 * NT;
+      float* red = reinterpret_cast<float*>(smem);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int t = 0; t < NT; ++t) red[((size_t)wave * SLOTS + (mt * 4 + r) * NT + t) * 64 + lane] = acc[mt][t][r];
+      __syncthreads();
+      for (int q = kq; q < MT * 4; q += KW) {               // this wave finishes rows q of its column set
+        float v[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          float sum = 0.f;
+#pragma unroll
+          for (int k = 0; k < KW; ++k) sum += red[((size_t)(cs * KW + k) * SLOTS + q * NT + t) * 64 + lane];
+          v[t] = sum;
+        }
+        emit(q >> 2, q & 3, v);
       }
     }
   } else {
@@ -213,48 +293,74 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_bf16(GemmArgs a) {
   }
 }
 
-template <int NT, int WAVES, int KC, int PF, bool ARGMAX>
+template <int NT, int CS, int KW, int KC, int PF, int MODE>
 void launch_mt(int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
+  const dim3 block(64 * CS * KW);
   switch (mt) {
-    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
-    case 3: hipLaunchKernelGGL((k_gemm_bf16<3, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<5, NT, WAVES, KC, PF, ARGMAX>), grid, dim3(64 * WAVES), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, NT, CS, KW, KC, PF, MODE>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, NT, CS, KW, KC, PF, MODE>), grid, block, 0, s, a); break;
+    case 3: hipLaunchKernelGGL((k_gemm_bf16<3, NT, CS, KW, KC, PF, MODE>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((k_gemm_bf16<4, NT, CS, KW, KC, PF, MODE>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm_bf16<5, NT, CS, KW, KC, PF, MODE>), grid, block, 0, s, a); break;
   }
 }
 
-// The compiled tile shapes.  shape id -> (NT, WAVES, KC, PF).  The LDS holds two buffers of
-// two planes of the activation chunk, which keeps KC at 128 for 80 rows.
-constexpr int kNumShapes = 4;
-const int kShapeNT[kNumShapes] = {1, 2, 1, 2};
-const int kShapeWaves[kNumShapes] = {4, 4, 8, 8};
-const int kShapeKC[kNumShapes] = {128, 128, 128, 128};
+// The compiled tile shapes.  shape id -> (NT, CS, KW): tiles per wave, column sets and
+// k-waves per workgroup.  All use chunks of 128 k (the LDS holds two buffers of two planes of
+// the activation chunk, 85 KiB for 80 rows).  The k-wave shapes hold fewer weight registers
+// per chunk and prefetch several chunks ahead instead.
+#ifdef TS_GEMM_EXPERIMENT
+constexpr int kNumShapes = 8;
+#else
+constexpr int kNumShapes = 5;
+#endif
+const int kShapeNT[8] = {1, 2, 1, 2, 2, 2, 2, 2};
+const int kShapeCS[8] = {4, 4, 8, 8, 4, 8, 4, 4};
+const int kShapeKW[8] = {1, 1, 1, 1, 2, 1, 2, 2};
+const int kShapeKC[8] = {128, 128, 128, 128, 128, 64, 128, 64};
 
-template <bool ARGMAX>
+template <int MODE>
 void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
   switch (shape) {
-    case 0: launch_mt<1, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
-    case 1: launch_mt<2, 4, 128, 1, ARGMAX>(mt, grid, s, a); break;
-    case 2: launch_mt<1, 8, 128, 1, ARGMAX>(mt, grid, s, a); break;
-    default: launch_mt<2, 8, 128, 1, ARGMAX>(mt, grid, s, a); break;
+    case 0: if (MODE != MODE_SWIGLU) launch_mt<1, 4, 1, 128, 1, MODE == MODE_SWIGLU ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
+    case 1: launch_mt<2, 4, 1, 128, 1, MODE>(mt, grid, s, a); break;
+    case 2: if (MODE != MODE_SWIGLU) launch_mt<1, 8, 1, 128, 1, MODE == MODE_SWIGLU ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
+    case 3: launch_mt<2, 8, 1, 128, 1, MODE>(mt, grid, s, a); break;
+    case 4: if (MODE != MODE_ARGMAX) launch_mt<2, 4, 2, 128, 2, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
+#ifdef TS_GEMM_EXPERIMENT
+    case 5: launch_mt<2, 8, 1, 64, 3, MODE>(mt, grid, s, a); break;
+    case 6: if (MODE != MODE_ARGMAX) launch_mt<2, 4, 2, 128, 3, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
+    case 7: if (MODE != MODE_ARGMAX) launch_mt<2, 4, 2, 64, 5, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
+#endif
+    default: break;
   }
+}
+
+bool shape_supports(int shape, int mode) {
+  if (mode == MODE_ARGMAX) return kShapeKW[shape] == 1;
+  if (mode == MODE_SWIGLU) return kShapeNT[shape] == 2;
+  return true;
 }
 
 }  // namespace
 
-int gemm_bf16_cols_per_group(int shape) { return kShapeNT[shape] * kShapeWaves[shape] * 16; }
+int gemm_bf16_cols_per_group(int shape) { return kShapeNT[shape] * kShapeCS[shape] * 16; }
 int gemm_bf16_chunk(int shape) { return kShapeKC[shape]; }
 
-// Tile shape and K splits.  Measured on MI355X, the stream is fastest when the workgroups
-// of a launch fit the chip in ONE round (one 8-wave workgroup per CU): a second round adds
-// a tail and more partial-sum traffic than it gains.  So: the (shape, splits) pair with the
-// most workgroups not exceeding the CU count, wider tiles winning ties; if even the
-// coarsest split exceeds the chip (lm_head), the fewest workgroups.
-GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K, bool allow_split) {
-  GemmPlan best{0, 1};
-  long best_score = -1;
-  for (int shape = 0; shape < kNumShapes; ++shape) {
+// Tile shape and cross-workgroup K splits, from a byte count per CU:
+//   rounds x (weight bytes one workgroup streams)         rounds = ceil(workgroups / CUs)
+// + write and read of the fp32 partial sums, shared by all CUs (only if splits > 1)
+// + a quarter of the activation bytes a workgroup stages from L2 per round.
+// Measured on MI355X, a second round of workgroups costs a full round (the tail does not
+// overlap), which the round count models.  mode: 0 partial sums, 1 arg-max (no split),
+// 2 SwiGLU epilogue (no split).
+GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
+  GemmPlan best{mode == MODE_SWIGLU ? 1 : 0, 1};
+  double best_cost = 1e300;
+  const int rows = R > TS_MROWS_PER_BLOCK ? TS_MROWS_PER_BLOCK : ((R + 15) / 16) * 16;
+  const int m_blocks = (R + TS_MROWS_PER_BLOCK - 1) / TS_MROWS_PER_BLOCK;   // each streams the weights again
+  for (int shape = 0; shape < 5; ++shape) {
+    if (!shape_supports(shape, mode)) continue;
     const int kc = kShapeKC[shape];
     if (K % kc) continue;
     const int chunks = K / kc;
@@ -262,25 +368,31 @@ GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K, bool allow_split) {
     const int groups = (N + cols - 1) / cols;
     for (int s = 1; s <= chunks && s <= 16; ++s) {
       if (chunks % s) continue;
-      if (!allow_split && s > 1) break;
-      const long wgs = (long)groups * s;
-      // fits in one round: more workgroups is better; otherwise fewer is better
-      long score = wgs <= m->n_cu ? (1L << 40) + wgs * 16 : (1L << 30) - wgs * 16;
-      score += kShapeWaves[shape] + kShapeNT[shape];        // prefer 8 waves, 2 tiles on ties
-      if (score > best_score) { best_score = score; best.shape = shape; best.splits = s; }
+      if (mode != MODE_PARTIAL && s > 1) break;
+      const long wgs = (long)groups * s * m_blocks;
+      const long rounds = (wgs + m->n_cu - 1) / m->n_cu;
+      const double kper = (double)K / s;
+      double cost = rounds * cols * kper * 2.0;
+      if (s > 1) cost += 2.0 * s * R * (double)N * 4.0 / m->n_cu;
+      cost += 0.25 * rounds * rows * kper * 4.0;
+      if (kShapeCS[shape] * kShapeKW[shape] < 8) cost *= 1.05;   // 4-wave workgroups hide less latency
+      if (kShapeNT[shape] < 2) cost *= 1.05;                     // one tile per wave reads twice the LDS per weight byte
+      if (cost < best_cost) { best_cost = cost; best.shape = shape; best.splits = s; }
     }
   }
   return best;
 }
 
 void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, GemmPlan plan,
-                      bool argmax, float* logits) {
+                      int mode, float* logits, bf16_t* act_out) {
   GemmArgs a;
   a.x_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * K;
   a.X = X; a.Wt = Wt; a.out = out; a.logits = logits;
   a.aval = m->amax_val; a.aidx = m->amax_idx;
+  a.act_out = act_out;
+  a.act_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * (N / 2);
   a.R = R; a.N = N; a.K = K;
-  const int splits = argmax ? 1 : plan.splits;
+  const int splits = mode == MODE_PARTIAL ? plan.splits : 1;
   a.kper = K / splits;
   a.n_tiles = (N + 15) / 16;
   a.kt_count = K / 32;
@@ -291,6 +403,7 @@ void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out
   const int m_blocks = (R + TS_MROWS_PER_BLOCK - 1) / TS_MROWS_PER_BLOCK;
   const int mt = m_blocks > 1 ? 5 : (R + 15) / 16;
   dim3 grid(groups, splits, m_blocks);
-  if (argmax) launch_shape<true>(plan.shape, mt, grid, m->stream, a);
-  else launch_shape<false>(plan.shape, mt, grid, m->stream, a);
+  if (mode == MODE_ARGMAX) launch_shape<MODE_ARGMAX>(plan.shape, mt, grid, m->stream, a);
+  else if (mode == MODE_SWIGLU) launch_shape<MODE_SWIGLU>(plan.shape, mt, grid, m->stream, a);
+  else launch_shape<MODE_PARTIAL>(plan.shape, mt, grid, m->stream, a);
 }

@@ -150,7 +150,12 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs) {
     if (c.dtype == TS_DTYPE_BF16) {
       const int Ns[4] = {m->qkv_dim, c.d_model, 2 * c.d_ffn, c.d_model};
       const int Ks[4] = {c.d_model, m->q_dim, c.d_model, c.d_ffn};
-      for (int i = 0; i < 4; ++i) pe = std::max(pe, (size_t)gemm_bf16_plan(m, Ns[i], Ks[i], true).splits * cap * Ns[i]);
+      // the plan depends on the row count of a call; project() falls back to fewer splits if a
+      // plan would not fit, so size for the planned splits at capacity and for 16 splits of one row block
+      for (int i = 0; i < 4; ++i) {
+        pe = std::max(pe, (size_t)gemm_bf16_plan(m, cap, Ns[i], Ks[i], 0).splits * cap * Ns[i]);
+        pe = std::max(pe, (size_t)16 * std::min(cap, TS_MROWS_PER_BLOCK) * Ns[i]);
+      }
     } else {
       pe = (size_t)cap * std::max(std::max(m->qkv_dim, 2 * c.d_ffn), c.d_model);
     }
@@ -339,7 +344,7 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   }
   m->n_cu = prop.multiProcessorCount;
   if (cfg->dtype == TS_DTYPE_BF16) {
-    const GemmPlan p = gemm_bf16_plan(m, cfg->vocab, cfg->d_model, false);
+    const GemmPlan p = gemm_bf16_plan(m, TS_MROWS_PER_BLOCK, cfg->vocab, cfg->d_model, 1);
     const int cols = gemm_bf16_cols_per_group(p.shape);
     m->amax_parts = (cfg->vocab + cols - 1) / cols;
   } else {
@@ -605,9 +610,10 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   size_t pending_stride = 0;
   auto project = [&](const char* name, const void* X, const void* W, int N, int K, int* n_parts, size_t* stride) {
     if (bf) {
-      const GemmPlan p = gemm_bf16_plan(m, N, K, true);
+      GemmPlan p = gemm_bf16_plan(m, R, N, K, 0);
+      while (p.splits > 1 && (size_t)p.splits * R * N > m->part_elems) p.splits = K / gemm_bf16_chunk(p.shape) % (p.splits / 2) == 0 ? p.splits / 2 : 1;
       ProfScope ps(m, name);
-      launch_gemm_bf16(m, (const bf16_t*)X, (const bf16_t*)W, m->part, R, N, K, p, false, nullptr);
+      launch_gemm_bf16(m, (const bf16_t*)X, (const bf16_t*)W, m->part, R, N, K, p, 0, nullptr, nullptr);
       *n_parts = p.splits;
       *stride = (size_t)R * N;
     } else {
@@ -630,16 +636,22 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     }
     project("gemm_o", m->Ab, L.wo, d, m->q_dim, &np, &ps);
     launch_norm(m, R, L.norm2, np, ps, false);
-    project("gemm_gate_up", m->Xn, L.wgu, 2 * F, d, &np, &ps);
-    launch_swiglu(m, R, np, ps);
+    if (bf) {   // gate/up projection with the SwiGLU product in its epilogue
+      const GemmPlan p = gemm_bf16_plan(m, R, 2 * F, d, 2);
+      ProfScope psc(m, "gemm_gate_up");
+      launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)L.wgu, nullptr, R, 2 * F, d, p, 2, nullptr, (bf16_t*)m->Fb);
+    } else {
+      project("gemm_gate_up", m->Xn, L.wgu, 2 * F, d, &np, &ps);
+      launch_swiglu(m, R, np, ps);
+    }
     project("gemm_down", m->Fb, L.wd, d, F, &pending_parts, &pending_stride);
   }
   launch_norm(m, R, m->norm_f, pending_parts, pending_stride, false);
   if (bf) {
-    const GemmPlan p = gemm_bf16_plan(m, c.vocab, d, false);
+    const GemmPlan p = gemm_bf16_plan(m, TS_MROWS_PER_BLOCK, c.vocab, d, 1);   // as at load: fixes the partial count
     ProfScope ps(m, "gemm_lm_head_argmax");
-    launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)m->lm_head, nullptr, R, c.vocab, d, p, true,
-                     m->keep_logits ? m->logits : nullptr);
+    launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)m->lm_head, nullptr, R, c.vocab, d, p, 1,
+                     m->keep_logits ? m->logits : nullptr, nullptr);
   } else {
     launch_gemm_f32(m, (const float*)m->Xn, (const float*)m->lm_head, m->logits, R, c.vocab, d);
     launch_argmax_rows(m, R);

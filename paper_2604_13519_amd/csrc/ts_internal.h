@@ -129,11 +129,12 @@ void launch_attn_f32(ts_model* m, const RowMeta& rm, int R, int n_seqs, int laye
 size_t attn_f32_max_keys();
 // bf16 compute path (ts_gemm_bf16.hip / ts_attn_bf16.hip)
 struct GemmPlan { int shape; int splits; };   // compiled tile shape id, K splits
-GemmPlan gemm_bf16_plan(const ts_model* m, int N, int K, bool allow_split);
+// mode: 0 = fp32 partial sums [split][R][N], 1 = fused arg-max (lm_head), 2 = SwiGLU epilogue (gate/up)
+GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode);
 int gemm_bf16_cols_per_group(int shape);
 int gemm_bf16_chunk(int shape);
 void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K,
-                      GemmPlan plan, bool argmax, float* logits);
+                      GemmPlan plan, int mode, float* logits, bf16_t* act_out);
 int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs);
 void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int layer, int splits, int max_M);
 void launch_attn_merge(ts_model* m, int R, int splits);
