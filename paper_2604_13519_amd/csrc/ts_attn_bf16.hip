@@ -295,43 +295,74 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
   }
 }
 
-// Combine the splits: out = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s, stored as bf16.
+// Combine the splits: out = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s, stored as (hi, lo) bf16.
+// One workgroup per (row, head): its 256 threads form 256/(HD/4) groups, group j takes splits
+// j, j+groups, ... so that every partial of the slot is requested at once (the kernel is a
+// single round of memory latency plus the transfer); the groups' sums are then added through
+// LDS in a fixed order.
+constexpr int kMergeMaxSplits = 512;
+
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                     bf16_t* __restrict__ Ab, size_t lo_plane, int R, int Hq, int HD, int splits) {
-  // one (row, head) pair per group of HD/4 threads, 16-byte accesses
-  const int tpp = HD / 4;
+  __shared__ float s_m[kMergeMaxSplits], s_l[kMergeMaxSplits];
+  __shared__ float4 r_num[256];
+  __shared__ float r_den[256];
+  const int tid = threadIdx.x;
+  const int tpp = HD / 4;                  // threads per group: one float4 of the head each
+  const int groups = 256 / tpp;
+  const int grp = tid / tpp, d4 = tid % tpp;
   const size_t n_slots = (size_t)R * Hq;
-  const size_t slot = (size_t)blockIdx.x * (256 / tpp) + threadIdx.x / tpp;
-  const int d4 = threadIdx.x % tpp;
-  if (slot >= n_slots) return;
+  const size_t slot = blockIdx.x;
   const float2* ml = reinterpret_cast<const float2*>(part_ml);
   const float4* po = reinterpret_cast<const float4*>(part_o);
+  for (int sp = tid; sp < splits; sp += 256) {
+    const float2 v = ml[(size_t)sp * n_slots + slot];
+    s_m[sp] = v.x;
+    s_l[sp] = v.y;
+  }
+  float4 o4[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int sp = grp + u * groups;
+    o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __syncthreads();
   float mstar = -INFINITY;
-  for (int s = 0; s < splits; ++s) mstar = fmaxf(mstar, ml[s * n_slots + slot].x);
+  for (int sp = 0; sp < splits; ++sp) mstar = fmaxf(mstar, s_m[sp]);
   float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
-  for (int s0 = 0; s0 < splits; s0 += 8) {
-    float2 m8[8];
-    float4 o8[8];
+  for (int s0 = 0; s0 < splits; s0 += 4 * groups) {
+    if (s0 > 0) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const size_t base = (size_t)(s0 + u < splits ? s0 + u : s0) * n_slots + slot;
-      m8[u] = ml[base];
-      o8[u] = po[base * tpp + d4];
+      for (int u = 0; u < 4; ++u) {
+        const int sp = s0 + grp + u * groups;
+        o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      // whole-number references: an exact power of two
-      const float w = (s0 + u < splits && m8[u].x != -INFINITY) ? exp2f(m8[u].x - mstar) : 0.f;
-      den += w * m8[u].y;
-      num.x += w * o8[u].x; num.y += w * o8[u].y; num.z += w * o8[u].z; num.w += w * o8[u].w;
+    for (int u = 0; u < 4; ++u) {
+      const int sp = s0 + grp + u * groups;
+      if (sp < splits && s_m[sp] != -INFINITY) {
+        const float w = exp2f(s_m[sp] - mstar);          // whole-number references: an exact power of two
+        den += w * s_l[sp];
+        num.x += w * o4[u].x; num.y += w * o4[u].y; num.z += w * o4[u].z; num.w += w * o4[u].w;
+      }
     }
   }
+  r_num[tid] = num;
+  r_den[tid] = den;
+  __syncthreads();
+  if (grp != 0) return;
+  for (int k = 1; k < groups; ++k) {
+    const float4 t = r_num[k * tpp + d4];
+    num.x += t.x; num.y += t.y; num.z += t.z; num.w += t.w;
+    den += r_den[k * tpp + d4];
+  }
   // the attention output feeds the O projection: (hi, lo) bf16 planes
-  const float o4[4] = {num.x / den, num.y / den, num.z / den, num.w / den};
+  const float o[4] = {num.x / den, num.y / den, num.z / den, num.w / den};
   bf16_t hi[4], lo[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) split_bf16(o4[i], hi[i], lo[i]);
+  for (int i = 0; i < 4; ++i) split_bf16(o[i], hi[i], lo[i]);
   uint2 oh, ol;
   oh.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); oh.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
   ol.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); ol.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
@@ -384,6 +415,7 @@ int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs) {
     const int cap = atoi(e);
     if (cap >= 1 && want > cap) want = cap;
   }
+  if (want > kMergeMaxSplits) want = kMergeMaxSplits;      // the merge kernel keeps (max, sum) of every split in LDS
   const int bps = (n_blk + want - 1) / want;
   return (n_blk + bps - 1) / bps;
 }
@@ -409,7 +441,6 @@ void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int lay
 void launch_attn_merge(ts_model* m, int R, int splits) {
   ProfScope ps(m, "attn_merge");
   const ts_model_config& c = m->cfg;
-  const int per_block = 256 / (c.head_dim / 4);
-  hipLaunchKernelGGL(k_attn_merge, dim3((R * c.n_q_heads + per_block - 1) / per_block), dim3(256), 0, m->stream, m->attn_part_o, m->attn_part_ml,
+  hipLaunchKernelGGL(k_attn_merge, dim3(R * c.n_q_heads), dim3(256), 0, m->stream, m->attn_part_o, m->attn_part_ml,
                      (bf16_t*)m->Ab, act_plane(m, m->q_dim), R, c.n_q_heads, c.head_dim, splits);
 }

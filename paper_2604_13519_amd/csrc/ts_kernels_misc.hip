@@ -288,40 +288,55 @@ __global__ __launch_bounds__(1024) void k_walk(const float* __restrict__ aval, c
                                                const int32_t* __restrict__ par, const int32_t* __restrict__ depth,
                                                const SeqDesc* __restrict__ seqs) {
   __shared__ int g[TS_MAX_NODES + 1];
+  __shared__ int s_tok[TS_MAX_NODES + 1], s_par[TS_MAX_NODES + 1], s_dep[TS_MAX_NODES + 1];
   __shared__ unsigned char valid[TS_MAX_NODES + 1];
   const SeqDesc sd = seqs[blockIdx.x];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x < sd.M) {                           // the serial walk below reads the tree from LDS
+    s_tok[threadIdx.x] = tok[sd.row0 + threadIdx.x];
+    s_par[threadIdx.x] = par[sd.row0 + threadIdx.x];
+    s_dep[threadIdx.x] = depth[sd.row0 + threadIdx.x];
+  }
   for (int r = wave; r < sd.M; r += 16) {            // one wave per row, lanes stride over the partials
     const size_t base = (size_t)(sd.row0 + r) * parts;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int p = lane; p < used_parts; p += 64) amax_take(bv, bi, aval[base + p], aidx[base + p]);
+    for (int p0 = 0; p0 < used_parts; p0 += 64 * 8) { // 8 independent loads per lane in flight
+      float v8[8];
+      int i8[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int p = p0 + j * 64 + lane;
+        const bool ok = p < used_parts;
+        v8[j] = ok ? aval[base + p] : -INFINITY;
+        i8[j] = ok ? aidx[base + p] : 0x7fffffff;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) amax_take(bv, bi, v8[j], i8[j]);
+    }
     wave_amax(bv, bi);
     if (lane == 0) g[r] = bi;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    const int32_t* t = tok + sd.row0;
-    const int32_t* pa = par + sd.row0;
-    const int32_t* de = depth + sd.row0;
     int best = 0;
     valid[0] = 1;
     for (int r = 1; r < sd.M; ++r) {
-      const int p = pa[r];
-      const unsigned char v = valid[p] && (t[r] == g[p]);
+      const int p = s_par[r];
+      const unsigned char v = valid[p] && (s_tok[r] == g[p]);
       valid[r] = v;
-      if (v && de[r] > de[best]) best = r;
+      if (v && s_dep[r] > s_dep[best]) best = r;
     }
     int32_t* res = sd.result;
-    const int len = de[best];
+    const int len = s_dep[best];
     res[0] = len;
     res[1] = g[best];
     res[2] = best;
     int r = best;
     for (int dd = len; dd >= 1; --dd) {
       res[4 + dd - 1] = r;
-      res[4 + TS_MAX_NODES + dd - 1] = t[r];
-      r = pa[r];
+      res[4 + TS_MAX_NODES + dd - 1] = s_tok[r];
+      r = s_par[r];
     }
   }
 }
