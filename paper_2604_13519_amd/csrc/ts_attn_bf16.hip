@@ -31,6 +31,8 @@
 // Partial (max, sum, O) per split are combined by k_attn_merge.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 
@@ -64,8 +66,10 @@ union Pack8 {
   uint32_t u[4];
 };
 
-template <int HD, int MT, int HB, int RS>
-__global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_bf16(AttnArgs a) {
+// MT0 row tiles for the waves of the first row split, MT1 (0 = no second split) for the second
+template <int HD, int MT0, int MT1, int HB>
+__global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1) <= 4) ? 2 : 1) void k_attn_bf16(AttnArgs a) {
+  constexpr int RS = MT1 > 0 ? 2 : 1;
   constexpr int KSQ = HD / 32;            // k-steps of the score product
   constexpr int DT = HD / 16;             // 16-dim tiles of the output
   constexpr int NTHR = 64 * HB * RS;
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
   const int split = rest % a.splits;
   const int g = (rest / a.splits) % a.Hkv;
   const int h = g * G + (jj % subs) * HB + (wave % HB);
-  const int tile0 = (wave / HB) * MT;     // first 16-row tile of this wave
+  const int tile0 = (wave / HB) * MT0;    // first 16-row tile of this wave
   const SeqDesc sd = a.seqs[rest / (a.splits * a.Hkv)];
   const int P = sd.P, M = sd.M, T = P + M;
   const int n_blk = (T + KB - 1) / KB;
@@ -106,6 +110,57 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
   const TS_GLOBAL bf16_t* vl = (const TS_GLOBAL bf16_t*)sd.v_pool + (size_t)a.layer * sd.n_pages * page_elems + (size_t)g * 16 * HD;
   const TS_GLOBAL int32_t* ptab = (const TS_GLOBAL int32_t*)sd.page_table;
 
+  // Staging of one key block (4 pages).  A thread always fetches the same vector of a page
+  // (K vectors for the first VPP thread ids, V vectors after), so its source pointer is fixed
+  // and a page only adds a wave-uniform offset: one scalar page-table load and no vector
+  // address arithmetic per page.  Pages past the last key are clamped to the last one: their
+  // keys are masked in the scores and their V entries (finite cache contents) meet zero
+  // probabilities.
+  const TS_GLOBAL bf16_t* my_src[JP];
+#pragma unroll
+  for (int j = 0; j < JP; ++j) {
+    const int w = min(tid + j * NTHR, VPG - 1);
+    my_src[j] = (w < VPP) ? (kl + (size_t)w * 8) : (vl + (size_t)(w - VPP) * 8);
+  }
+  // Page-table entries of a key block: one 16-byte load (the table is padded by four entries of
+  // page 0), fetched a block ahead of the data loads that need it and moved to scalar registers
+  // there.  Pages past the last key hold finite cache contents.
+  typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+  auto load_pt = [&](int blk) { return *reinterpret_cast<const TS_GLOBAL i32x4*>(ptab + blk * 4); };
+  u32x4 stage[NV];
+  auto load_block = [&](const i32x4& pt) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const size_t pg = (size_t)__builtin_amdgcn_readfirstlane(pt[p]) * page_elems;
+#pragma unroll
+      for (int j = 0; j < JP; ++j)
+        if (VPG % NTHR == 0 || tid + j * NTHR < VPG) stage[p * JP + j] = *reinterpret_cast<const TS_GLOBAL u32x4*>(my_src[j] + pg);
+    }
+  };
+  auto store_block = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int j = 0; j < JP; ++j) {
+        const int w = tid + j * NTHR;
+        if (VPG % NTHR != 0 && w >= VPG) continue;
+        if (w < VPP) {
+          const int t = w / (HD / 8), dv = w % (HD / 8);
+          *reinterpret_cast<u32x4*>(&ks_[buf][p * 16 + t][dv * 8]) = to_half8(stage[p * JP + j]);
+        } else {
+          const int w2 = w - VPP;
+          const u32x4 v = to_half8(stage[p * JP + j]);     // 8 tokens; rows are only 8-byte aligned
+          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8]) = u32x2{v.x, v.y};
+          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8 + 4]) = u32x2{v.z, v.w};
+        }
+      }
+  };
+
+  // The main loop, compiled once per tile count: the waves of the second row split usually own
+  // fewer tiles (5 tiles = 3 + 2) and run a copy without the empty one.  Both copies execute
+  // the same barriers.
+  auto body = [&](auto mt_c) {
+    constexpr int MT = decltype(mt_c)::value;
   // resident query fragments and ancestor masks of this wave's head
   f16x8 qf[MT][KSQ];
   uint64_t anc[MT];
@@ -132,48 +187,10 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
 #pragma unroll
   for (int i = 0; i < 4; ++i) ones.u[i] = 0x3c003c00u;   // half 1.0 x 8
 
-  // Staging of one key block (4 pages).  The page loop is wave-uniform, so each page-table
-  // entry is one scalar load and the data loads of all four pages go out back to back.
-  u32x4 stage[NV];
-  auto load_block = [&](int blk) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int lp = blk * 4 + p;
-      const bool ok = lp < sd.n_pages && lp * 16 < T;
-      const size_t pg = ok ? (size_t)ptab[lp] * page_elems : 0;
-#pragma unroll
-      for (int j = 0; j < JP; ++j) {
-        const int w = tid + j * NTHR;
-        u32x4 val = u32x4{0u, 0u, 0u, 0u};
-        if (ok && (VPG % NTHR == 0 || w < VPG)) {
-          const TS_GLOBAL bf16_t* src = (w < VPP) ? (kl + pg + (size_t)w * 8) : (vl + pg + (size_t)(w - VPP) * 8);
-          val = *reinterpret_cast<const TS_GLOBAL u32x4*>(src);
-        }
-        stage[p * JP + j] = val;
-      }
-    }
-  };
-  auto store_block = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-      for (int j = 0; j < JP; ++j) {
-        const int w = tid + j * NTHR;
-        if (VPG % NTHR != 0 && w >= VPG) continue;
-        if (w < VPP) {
-          const int t = w / (HD / 8), dv = w % (HD / 8);
-          *reinterpret_cast<u32x4*>(&ks_[buf][p * 16 + t][dv * 8]) = to_half8(stage[p * JP + j]);
-        } else {
-          const int w2 = w - VPP;
-          const u32x4 v = to_half8(stage[p * JP + j]);     // 8 tokens; rows are only 8-byte aligned
-          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8]) = u32x2{v.x, v.y};
-          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8 + 4]) = u32x2{v.z, v.w};
-        }
-      }
-  };
-
+  i32x4 pt_next = i32x4{0, 0, 0, 0};
   if (b0 < b1) {
-    load_block(b0);
+    load_block(load_pt(b0));
+    if (b0 + 1 < b1) pt_next = load_pt(b0 + 1);
     store_block(0);
   }
   __syncthreads();
@@ -181,7 +198,10 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
   for (int blk = b0; blk < b1; ++blk) {
     const int cur = (blk - b0) & 1;
     const bool more = blk + 1 < b1;
-    if (more) load_block(blk + 1);
+    if (more) {
+      load_block(pt_next);
+      if (blk + 2 < b1) pt_next = load_pt(blk + 2);
+    }
 
     // Two sub-blocks of 32 keys (2 pages) each: scores, mask, running soft-max, P.V.
     const int key0 = blk * KB;
@@ -293,6 +313,9 @@ __global__ __launch_bounds__(64 * HB * RS, (HB * RS <= 4) ? 2 : 1) void k_attn_b
         *reinterpret_cast<f32x4*>(a.part_o + base * HD + dt * 16 + g4 * 4) = o[dt][mt];
     }
   }
+  };
+  if (RS == 1 || wave / HB == 0) body(std::integral_constant<int, MT0>{});
+  else body(std::integral_constant<int, (MT1 > 0 ? MT1 : MT0)>{});
 }
 
 // Combine the splits: out = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s, stored as (hi, lo) bf16.
@@ -371,16 +394,16 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ pa
 }
 
 // Rows are covered by RS waves per head, MT tiles of 16 rows each: (tiles -> RS x MT)
-// 1 -> 1x1, 2 -> 1x2, 3 -> 1x3, 4 -> 2x2, 5 -> 2x3.  Two row-splits put two waves on every
+// 1 -> 1, 2 -> 2, 3 -> 3, 4 -> 2+2, 5 -> 3+2.  Two row-splits put two waves on every
 // SIMD (256 registers each) and let one wave's soft-max arithmetic overlap the other's MFMAs.
 template <int HD, int HB>
 void launch_hb(int tiles, dim3 grid, hipStream_t s, const AttnArgs& a) {
   switch (tiles) {
-    case 1: hipLaunchKernelGGL((k_attn_bf16<HD, 1, HB, 1>), grid, dim3(64 * HB), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((k_attn_bf16<HD, 2, HB, 1>), grid, dim3(64 * HB), 0, s, a); break;
-    case 3: hipLaunchKernelGGL((k_attn_bf16<HD, 3, HB, 1>), grid, dim3(64 * HB), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((k_attn_bf16<HD, 2, HB, 2>), grid, dim3(128 * HB), 0, s, a); break;
-    default: hipLaunchKernelGGL((k_attn_bf16<HD, 3, HB, 2>), grid, dim3(128 * HB), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((k_attn_bf16<HD, 1, 0, HB>), grid, dim3(64 * HB), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((k_attn_bf16<HD, 2, 0, HB>), grid, dim3(64 * HB), 0, s, a); break;
+    case 3: hipLaunchKernelGGL((k_attn_bf16<HD, 3, 0, HB>), grid, dim3(64 * HB), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((k_attn_bf16<HD, 2, 2, HB>), grid, dim3(128 * HB), 0, s, a); break;
+    default: hipLaunchKernelGGL((k_attn_bf16<HD, 3, 2, HB>), grid, dim3(128 * HB), 0, s, a); break;
   }
 }
 

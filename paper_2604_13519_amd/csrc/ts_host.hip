@@ -415,7 +415,8 @@ extern "C" ts_status ts_kv_alloc(ts_model* m, int32_t capacity, int32_t page_siz
   const size_t bytes = kv->layer_stride_elems * c.n_layers * m->esz;
   ts_status st = dev_alloc_bytes(&kv->k_pool, bytes, true);
   if (!st) st = dev_alloc_bytes(&kv->v_pool, bytes, true);
-  if (!st) st = dev_alloc_bytes((void**)&kv->page_table, (size_t)kv->n_pages * 4, false);
+  // the attention kernel fetches the table four entries (one key block) at a time: pad with page 0
+  if (!st) st = dev_alloc_bytes((void**)&kv->page_table, (size_t)(kv->n_pages + 4) * 4, true);
   if (!st) st = dev_alloc_bytes((void**)&kv->result, TS_RESULT_INTS * 4, true);
   if (!st) {
     kv->page_table_host.resize(kv->n_pages);

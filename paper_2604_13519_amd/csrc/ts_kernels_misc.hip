@@ -15,6 +15,15 @@ __device__ __forceinline__ void st_q(bf16_t* p, float v) { *p = f32_to_f16_bits(
 // store an activation that feeds a projection: float as is, bf16 as a (hi, lo) pair of planes
 __device__ __forceinline__ void st_act(float* p, size_t, float v) { *p = v; }
 __device__ __forceinline__ void st_act(bf16_t* p, size_t lo_plane, float v) { split_bf16(v, p[0], p[lo_plane]); }
+// four consecutive activations (p 16-byte aligned in float terms): one vector store per plane
+__device__ __forceinline__ void st_act4(float* p, size_t, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st_act4(bf16_t* p, size_t lo_plane, const float4& v) {
+  bf16_t hi[4], lo[4];
+  split_bf16(v.x, hi[0], lo[0]); split_bf16(v.y, hi[1], lo[1]);
+  split_bf16(v.z, hi[2], lo[2]); split_bf16(v.w, hi[3], lo[3]);
+  *reinterpret_cast<uint2*>(p) = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+  *reinterpret_cast<uint2*>(p + lo_plane) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+}
 
 // ---------------------------------------------------------------------------------
 // weight re-tiling (model load): row-major [N][K] bf16 -> MFMA operand tiles.
@@ -101,10 +110,15 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
   const int r = blockIdx.x;
   float4* h4 = reinterpret_cast<float4*>(H + (size_t)r * d);
   const float4* p4 = reinterpret_cast<const float4*>(part + (size_t)r * d);
+  const float4* g4 = reinterpret_cast<const float4*>(gain);
   const size_t stride4 = part_stride / 4;
   const int d4 = d / 4;
+  // the first KEEP vectors of a thread stay in registers between the two passes (d_model up
+  // to 8192 never re-reads the residual); their gains are requested together with the data
+  constexpr int KEEP = 2;
+  float4 keep[KEEP], gk[KEEP];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d4; i += 1024) {
+  auto updated = [&](int i) {
     float4 v = h4[i];
     if (n_parts > 0) {
       // all partial loads of a batch are issued before the first add (fixed summation order)
@@ -119,7 +133,14 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
       h4[i] = v;
     }
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    return v;
+  };
+#pragma unroll
+  for (int k = 0; k < KEEP; ++k) {
+    const int i = threadIdx.x + k * 1024;
+    if (i < d4) { gk[k] = g4[i]; keep[k] = updated(i); }
   }
+  for (int i = threadIdx.x + KEEP * 1024; i < d4; i += 1024) updated(i);
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
@@ -127,15 +148,15 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
 #pragma unroll
   for (int w = 0; w < 16; ++w) tot += red[w];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  const float4* g4 = reinterpret_cast<const float4*>(gain);
-  for (int i = threadIdx.x; i < d4; i += 1024) {
-    const float4 v = h4[i], g = g4[i];
-    T* o = Xn + (size_t)r * d + 4 * i;
-    st_act(o + 0, lo_plane, v.x * inv * g.x);
-    st_act(o + 1, lo_plane, v.y * inv * g.y);
-    st_act(o + 2, lo_plane, v.z * inv * g.z);
-    st_act(o + 3, lo_plane, v.w * inv * g.w);
+  auto emit = [&](int i, const float4& v, const float4& g) {
+    st_act4(Xn + (size_t)r * d + 4 * i, lo_plane, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
+  };
+#pragma unroll
+  for (int k = 0; k < KEEP; ++k) {
+    const int i = threadIdx.x + k * 1024;
+    if (i < d4) emit(i, keep[k], gk[k]);
   }
+  for (int i = threadIdx.x + KEEP * 1024; i < d4; i += 1024) emit(i, h4[i], g4[i]);
 }
 
 void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part_stride, bool) {
