@@ -193,6 +193,11 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
     if (b0 + 1 < b1) pt_next = load_pt(b0 + 1);
     store_block(0);
   }
+  // Every load issued so far (query fragments, ancestor masks, first block) is complete past
+  // this point.  Without the explicit wait the compiler has to assume, at the loop head, that
+  // the query loads may still be in flight, and guards the first MFMA of every pass with a
+  // wait for ALL vector loads - which would include the next block's K/V just requested.
+  __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
   __syncthreads();
 
   for (int blk = b0; blk < b1; ++blk) {
