@@ -64,6 +64,9 @@ CONFIGS = {
     # workload 5: 32B-class shape (q_dim 8192 != d_model)
     "qwen32b": ModelConfig("qwen32b", 64, 5120, 64, 8, 128, 25600, 151936,
                            rope_theta=1000000.0, dtype=DTYPE_BF16),
+    # the first 8 layers of the 32B-class shape (same per-layer and lm_head launch shapes)
+    "qwen32b_8l": ModelConfig("qwen32b_8l", 8, 5120, 64, 8, 128, 25600, 151936,
+                              rope_theta=1000000.0, dtype=DTYPE_BF16),
     # ---- small parity shapes -------------------------------------------------
     # fp32, GQA 2:1, ragged vocab, random norm gains
     "micro_fp32": ModelConfig("micro_fp32", 2, 64, 4, 2, 16, 96, 131,
