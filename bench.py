@@ -197,7 +197,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(dom)
+            traffic = json.load(open(tpath)).get(dom, {}).get("bytes")   # rocprofv3 counter passes, see profiles/
         except Exception:
             traffic = None
     total_bytes = algorithmic_bytes(cfg, P)
