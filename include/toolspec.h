@@ -126,7 +126,7 @@ ts_status ts_kv_free(ts_kv* kv);
 /* Replace the identity page table by a permutation of [0, n_pages) (n_pages =
  * ceil(capacity/page_size)); only legal while the cache is empty. */
 ts_status ts_kv_set_page_table(ts_kv* kv, const int32_t* phys_page, int32_t n_pages);
-/* Test/bench helpers, needed because this library has no prefill of its own.
+/* Test/bench helpers: synthetic K/V for contexts whose real prefill the CPU oracle cannot afford.
  * k_host / v_host: [n_layers][n_pos][n_kv_heads][head_dim] in the model dtype,
  * K already rotated.  Import sets the committed length to n_pos. */
 ts_status ts_kv_import(ts_kv* kv, int32_t n_pos, const void* k_host, const void* v_host);
@@ -136,6 +136,14 @@ ts_status ts_kv_len(const ts_kv* kv, int32_t* committed_len);
 /* Roll the committed length back to new_len <= current length (drops later
  * positions, invalidates the last verify result); the caller sets the pending token. */
 ts_status ts_kv_truncate(ts_kv* kv, int32_t new_len);
+
+/* Context ingestion (the context x of Alg. 1: prompts and tool documentation, Sec. 4.1) through
+ * the verification kernels themselves: the sequence [pending token, if any] + tokens is run as
+ * causal chains of up to 65 rows, every row is kept (the K/V of all but the last token are
+ * appended to the cache), the last token becomes the pending token.  No logits are produced; the
+ * next ts_verify scores the pending token.  Errors (state unchanged): INVALID_ARG, TOKEN_RANGE,
+ * KV_CAPACITY (committed + appended + 1 > capacity), DEVICE. */
+ts_status ts_prefill(ts_model* m, ts_kv* kv, const int32_t* tokens, int32_t n_tokens);
 
 /* ---- verification (Alg. 1: Verification + SelectLongestAcceptedPrefix) --------
  * Scores root + n_nodes draft nodes in one forward pass and walks the longest

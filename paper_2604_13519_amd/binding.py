@@ -20,7 +20,7 @@ TS_MAX_NODES, TS_PAGE_SIZE = 64, 16
 
 EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits",
            "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export",
-           "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_verify", "ts_verify_batch",
+           "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_batch",
            "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read")
 
 
@@ -78,6 +78,7 @@ def load_library(path=None):
         "ts_set_pending": [C.c_void_p, C.c_int32],
         "ts_kv_len": [C.c_void_p, i32p],
         "ts_kv_truncate": [C.c_void_p, C.c_int32],
+        "ts_prefill": [C.c_void_p, C.c_void_p, i32p, C.c_int32],
         "ts_verify": [C.c_void_p, C.c_void_p, i32p, i32p, C.c_int32, i32p, i32p, i32p, i32p],
         "ts_verify_batch": [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, i32p, i32p, i32p, i32p, i32p, i32p, i32p],
         "ts_kv_commit": [C.c_void_p],
@@ -200,6 +201,11 @@ def ts_kv_len(kv):
 
 def ts_kv_truncate(kv, new_len):
     _check(load_library().ts_kv_truncate(kv, int(new_len)))
+
+
+def ts_prefill(model, kv, tokens):
+    t = _i32(tokens)
+    _check(load_library().ts_prefill(model, kv, _ptr_i32(t), len(t)))
 
 
 def ts_verify(model, kv, draft_tokens, parent_idx):

@@ -535,9 +535,11 @@ static RowMeta carve_meta(void* base, int rows) {
   return rm;
 }
 
+// ingest_only: run the layers (K/V of every row land in the tree slots) but not the final
+// norm, lm_head, arg-max and walk, and leave no verify result behind (context ingestion).
 static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const int32_t* toks, const int32_t* pars,
                              const int32_t* offs, int32_t* accept_len, int32_t* acc_tokens, int32_t* acc_nodes,
-                             int32_t* bonus) {
+                             int32_t* bonus, bool ingest_only = false) {
   const ts_model_config& c = m->cfg;
   const bool bf = c.dtype == TS_DTYPE_BF16;
   // ---- validation (nothing is modified before it passes) ---------------------------
@@ -647,6 +649,12 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     }
     project("gemm_down", m->Fb, L.wd, d, F, &pending_parts, &pending_stride);
   }
+  if (ingest_only) {
+    TS_HIP(hipGetLastError());
+    TS_HIP(hipStreamSynchronize(m->stream));
+    m->last_rows = 0;
+    return TS_OK;
+  }
   launch_norm(m, R, m->norm_f, pending_parts, pending_stride, false);
   if (bf) {
     const GemmPlan p = gemm_bf16_plan(m, TS_MROWS_PER_BLOCK, c.vocab, d, 1);   // as at load: fixes the partial count
@@ -708,6 +716,45 @@ extern "C" ts_status ts_verify_batch(ts_model* m, ts_kv* const* kvs, int32_t n_s
     if (node_offsets[s + 1] < node_offsets[s]) return ts_fail(TS_ERR_INVALID_ARG, "node_offsets must be non-decreasing");
   if (node_offsets[n_seqs] > 0 && !accepted_tokens) return ts_fail(TS_ERR_INVALID_ARG, "null accepted_tokens");
   return verify_impl(m, kvs, n_seqs, draft_tokens, parent_idx, node_offsets, accept_len, accepted_tokens, accepted_nodes, bonus_token);
+}
+
+// ---------------------------------------------------------------------------------
+// context ingestion through the same kernels: causal chains of up to 65 rows, every row kept
+// ---------------------------------------------------------------------------------
+extern "C" ts_status ts_prefill(ts_model* m, ts_kv* kv, const int32_t* tokens, int32_t n_tokens) {
+  if (!m || !kv || (n_tokens > 0 && !tokens)) return ts_fail(TS_ERR_INVALID_ARG, "ts_prefill: null argument");
+  if (kv->model != m) return ts_fail(TS_ERR_INVALID_ARG, "cache belongs to another model");
+  if (n_tokens < 0) return ts_fail(TS_ERR_INVALID_ARG, "n_tokens %d is negative", n_tokens);
+  if (n_tokens == 0) return TS_OK;
+  for (int i = 0; i < n_tokens; ++i)
+    if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab)
+      return ts_fail(TS_ERR_TOKEN_RANGE, "context token %d outside [0,%d) (index %d)", tokens[i], m->cfg.vocab, i);
+  // sequence to ingest: the pending token (if any), then tokens; the last one stays pending
+  std::vector<int32_t> seq;
+  seq.reserve((size_t)n_tokens + 1);
+  if (kv->pending >= 0) seq.push_back(kv->pending);
+  seq.insert(seq.end(), tokens, tokens + n_tokens);
+  const int rows_total = (int)seq.size() - 1;
+  if (kv->P + rows_total + 1 > kv->capacity)
+    return ts_fail(TS_ERR_KV_CAPACITY, "committed %d + context %d + 1 exceed the capacity %d", kv->P, rows_total, kv->capacity);
+  int32_t chain_par[TS_MAX_NODES];
+  for (int i = 0; i < TS_MAX_NODES; ++i) chain_par[i] = i - 1;
+  const int saved_P = kv->P, saved_pending = kv->pending;
+  int done = 0;
+  while (done < rows_total) {
+    const int rows = std::min(rows_total - done, TS_MAX_NODES + 1);
+    kv->pending = seq[done];
+    const int32_t offs[2] = {0, rows - 1};
+    ts_kv* kvs[1] = {kv};
+    int32_t dummy_len = 0, dummy_bonus = 0;
+    ts_status st = verify_impl(m, kvs, 1, seq.data() + done + 1, chain_par, offs, &dummy_len, nullptr, nullptr, &dummy_bonus, true);
+    if (st) { kv->P = saved_P; kv->pending = saved_pending; kv->have_result = false; return st; }
+    kv->P += rows;                                   // a chain's rows already sit in slots P .. P+rows-1
+    done += rows;
+  }
+  kv->pending = seq.back();
+  kv->have_result = false;
+  return TS_OK;
 }
 
 // ---------------------------------------------------------------------------------
