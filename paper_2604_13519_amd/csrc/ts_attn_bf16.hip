@@ -74,14 +74,16 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
   constexpr int DT = HD / 16;             // 16-dim tiles of the output
   constexpr int NTHR = 64 * HB * RS;
   constexpr int VPP = 2 * HD;             // 16-byte vectors per K page (and per V page)
-  constexpr int VTS = 20;                 // LDS row stride of a transposed V page, in tokens
+  constexpr int VTS = 40;                 // LDS row stride of the V^T of a 32-key half block, in tokens
   constexpr int VPG = 2 * VPP;            // 16-byte vectors per page, K then V
   constexpr int JP = (VPG + NTHR - 1) / NTHR;   // staged vectors per thread and page
   constexpr int NV = 4 * JP;              // staged vectors per thread and key block
   __shared__ __attribute__((aligned(16))) bf16_t ks_[2][KB][HD + 8];
-  // V^T rows are padded to 20 tokens (40 B): 16 lanes reading 8 B from 16 consecutive head-dim
-  // rows then fall into 16 distinct bank pairs (a 32 B stride would put them on 4)
-  __shared__ __attribute__((aligned(16))) bf16_t vs_[2][4][HD][VTS];
+  // V^T of a half block (2 pages = 32 keys): per head-dim row, the keys in the order the second
+  // MFMA wants them - lane group g holds tokens 4g..4g+3 of the first page, then of the second -
+  // so that a lane's operand is one 16-byte read.  Rows are padded to 40 tokens (80 B): 16 lanes
+  // reading 16 B from 16 consecutive rows then fall into 16 distinct groups of 4 banks.
+  __shared__ __attribute__((aligned(16))) bf16_t vs_[2][2][HD][VTS];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, g4 = lane >> 4;
@@ -149,9 +151,10 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
           *reinterpret_cast<u32x4*>(&ks_[buf][p * 16 + t][dv * 8]) = to_half8(stage[p * JP + j]);
         } else {
           const int w2 = w - VPP;
-          const u32x4 v = to_half8(stage[p * JP + j]);     // 8 tokens; rows are only 8-byte aligned
-          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8]) = u32x2{v.x, v.y};
-          *reinterpret_cast<u32x2*>(&vs_[buf][p][w2 >> 1][(w2 & 1) * 8 + 4]) = u32x2{v.z, v.w};
+          const u32x4 v = to_half8(stage[p * JP + j]);     // 8 tokens of one head-dim row
+          // tokens 8 (w2 & 1) .. +8 of page p: two groups of 4, lane groups 2 (w2 & 1) and 2 (w2 & 1) + 1
+          *reinterpret_cast<u32x2*>(&vs_[buf][p >> 1][w2 >> 1][(w2 & 1) * 16 + (p & 1) * 4]) = u32x2{v.x, v.y};
+          *reinterpret_cast<u32x2*>(&vs_[buf][p >> 1][w2 >> 1][(w2 & 1) * 16 + 8 + (p & 1) * 4]) = u32x2{v.z, v.w};
         }
       }
   };
@@ -290,8 +293,7 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         Pack8 va;
-        va.h[0] = *reinterpret_cast<const u32x2*>(&vs_[cur][2 * k2][dt * 16 + l15][g4 * 4]);
-        va.h[1] = *reinterpret_cast<const u32x2*>(&vs_[cur][2 * k2 + 1][dt * 16 + l15][g4 * 4]);
+        va.v = *reinterpret_cast<const f16x8*>(&vs_[cur][k2][dt * 16 + l15][g4 * 8]);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
           o[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb[mt].v, o[dt][mt], 0, 0, 0);
