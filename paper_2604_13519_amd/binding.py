@@ -58,7 +58,7 @@ def load_library(path=None):
     global _lib
     if _lib is not None:
         return _lib
-    path = path or LIB_PATH
+    path = path or os.environ.get("TS_LIB_PATH") or LIB_PATH   # TS_LIB_PATH: another build of the same library
     if not os.path.exists(path):
         raise RuntimeError("%s not found: build it with `python -m paper_2604_13519_amd.build`" % path)
     lib = C.CDLL(path)
