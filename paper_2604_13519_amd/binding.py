@@ -17,11 +17,15 @@ TS_ERR_INVALID_ARG, TS_ERR_INVALID_TREE, TS_ERR_TOKEN_RANGE = -1, -2, -3
 TS_ERR_KV_CAPACITY, TS_ERR_STATE, TS_ERR_OOM, TS_ERR_DEVICE = -4, -5, -6, -7
 TS_DTYPE_F32, TS_DTYPE_BF16 = 0, 1
 TS_MAX_NODES, TS_PAGE_SIZE = 64, 16
+TS_Q_OTHERS, TS_Q_TOOL_NAME, TS_Q_PARAM_NAME, TS_Q_PARAM_VALUE = 0, 1, 2, 3
+TS_DRAFT_NONE, TS_DRAFT_RETRIEVAL, TS_DRAFT_SCHEMA = 0, 1, 2
 
 EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits",
            "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export",
            "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_batch",
-           "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read")
+           "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read",
+           "ts_drafter_create", "ts_drafter_free", "ts_drafter_retrieve", "ts_drafter_reset",
+           "ts_drafter_append", "ts_drafter_state", "ts_drafter_draft")
 
 
 class TsError(RuntimeError):
@@ -44,6 +48,18 @@ class ts_weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("norm_f", C.c_void_p),
                 ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP), ("wg", _PP), ("wu", _PP),
                 ("wd", _PP), ("norm1", _PP), ("norm2", _PP)]
+
+
+_I32P = C.POINTER(C.c_int32)
+
+
+class ts_schema_desc(C.Structure):
+    _fields_ = [("call_open", _I32P), ("n_call_open", C.c_int32), ("name_prefix", _I32P), ("n_name_prefix", C.c_int32),
+                ("name_suffix", _I32P), ("n_name_suffix", C.c_int32), ("param_prefix", _I32P), ("n_param_prefix", C.c_int32),
+                ("param_suffix", _I32P), ("n_param_suffix", C.c_int32), ("value_end", _I32P), ("n_value_end", C.c_int32),
+                ("call_close", _I32P), ("n_call_close", C.c_int32), ("n_tools", C.c_int32),
+                ("tool_tokens", _I32P), ("tool_offsets", _I32P), ("param_first", _I32P),
+                ("param_tokens", _I32P), ("param_offsets", _I32P)]
 
 
 class ts_profile_entry(C.Structure):
@@ -85,6 +101,14 @@ def load_library(path=None):
         "ts_profile_enable": [C.c_void_p, C.c_int32],
         "ts_profile_filter": [C.c_void_p, C.c_char_p],
         "ts_profile_read": [C.c_void_p, C.POINTER(ts_profile_entry), C.c_int32, i32p],
+        "ts_drafter_create": [C.POINTER(ts_schema_desc), C.POINTER(C.c_void_p)],
+        "ts_drafter_free": [C.c_void_p],
+        "ts_drafter_retrieve": [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_float), C.c_int32, i32p, i32p,
+                                C.c_int32, i32p],
+        "ts_drafter_reset": [C.c_void_p],
+        "ts_drafter_append": [C.c_void_p, i32p, C.c_int32],
+        "ts_drafter_state": [C.c_void_p, i32p, i32p, i32p],
+        "ts_drafter_draft": [C.c_void_p, C.c_int32, i32p, i32p, i32p, i32p],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -265,3 +289,87 @@ def ts_profile_read(model, max_entries=64):
     n = C.c_int32()
     _check(load_library().ts_profile_read(model, arr, max_entries, C.byref(n)))
     return {arr[i].name.decode(): (arr[i].launches, arr[i].total_ms) for i in range(min(n.value, max_entries))}
+
+
+# --------------------------------------------------------------------------------------
+# host drafter (include/toolspec_draft.h): marshalling only
+# --------------------------------------------------------------------------------------
+def _pack(seqs):
+    """List of token sequences -> (concatenated int32 array, offsets int32[n+1])."""
+    offs = np.zeros(len(seqs) + 1, np.int32)
+    for i, q in enumerate(seqs):
+        offs[i + 1] = offs[i] + len(q)
+    toks = _i32(np.concatenate([_i32(q) for q in seqs]) if offs[-1] else np.zeros(0, np.int32))
+    return toks, offs
+
+
+def ts_drafter_create(schema):
+    """schema: dict with token lists call_open, name_prefix, name_suffix, param_prefix, param_suffix,
+    value_end, call_close, tools (list of token lists), params (per tool: list of token lists)."""
+    keep = []
+
+    def seq(name):
+        a = _i32(schema[name])
+        keep.append(a)
+        return _ptr_i32(a), len(a)
+
+    d = ts_schema_desc()
+    for f in ("call_open", "name_prefix", "name_suffix", "param_prefix", "param_suffix", "value_end", "call_close"):
+        p, n = seq(f)
+        setattr(d, f, p)
+        setattr(d, "n_" + f, n)
+    tt, to = _pack(schema["tools"])
+    first = np.zeros(len(schema["tools"]) + 1, np.int32)
+    flat = []
+    for i, ps in enumerate(schema["params"]):
+        first[i + 1] = first[i] + len(ps)
+        flat += list(ps)
+    pt, po = _pack(flat)
+    keep += [tt, to, first, pt, po]
+    d.n_tools = len(schema["tools"])
+    d.tool_tokens, d.tool_offsets, d.param_first = _ptr_i32(tt), _ptr_i32(to), _ptr_i32(first)
+    d.param_tokens, d.param_offsets = _ptr_i32(pt), _ptr_i32(po)
+    out = C.c_void_p()
+    _check(load_library().ts_drafter_create(C.byref(d), C.byref(out)))
+    return out
+
+
+def ts_drafter_free(drafter):
+    _check(load_library().ts_drafter_free(drafter))
+
+
+def ts_drafter_retrieve(drafter, h_x, H, calls, k=10):
+    """Returns the retrieved indices (most similar first)."""
+    h = np.ascontiguousarray(h_x, np.float32)
+    Hm = np.ascontiguousarray(H, np.float32).reshape(-1, h.shape[0])
+    yt, yo = _pack(calls)
+    top = np.zeros(max(k, 1), np.int32)
+    fp = C.POINTER(C.c_float)
+    _check(load_library().ts_drafter_retrieve(drafter, h.ctypes.data_as(fp), h.shape[0], Hm.ctypes.data_as(fp), Hm.shape[0],
+                                              _ptr_i32(yt), _ptr_i32(yo), k, _ptr_i32(top)))
+    return top[:min(k, Hm.shape[0])].tolist()
+
+
+def ts_drafter_reset(drafter):
+    _check(load_library().ts_drafter_reset(drafter))
+
+
+def ts_drafter_append(drafter, tokens):
+    t = _i32(tokens)
+    _check(load_library().ts_drafter_append(drafter, _ptr_i32(t), len(t)))
+
+
+def ts_drafter_state(drafter):
+    """(state, tool, len(y))."""
+    s, t, n = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load_library().ts_drafter_state(drafter, C.byref(s), C.byref(t), C.byref(n)))
+    return s.value, t.value, n.value
+
+
+def ts_drafter_draft(drafter, max_nodes=TS_MAX_NODES):
+    """(draft_tokens, parent_idx, source)."""
+    toks = np.zeros(max(max_nodes, 1), np.int32)
+    par = np.zeros(max(max_nodes, 1), np.int32)
+    n, src = C.c_int32(), C.c_int32()
+    _check(load_library().ts_drafter_draft(drafter, max_nodes, _ptr_i32(toks), _ptr_i32(par), C.byref(n), C.byref(src)))
+    return toks[:n.value].copy(), par[:n.value].copy(), src.value

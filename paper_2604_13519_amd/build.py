@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libtoolspec_hip.so")
-SOURCES = ["ts_host.hip", "ts_kernels_misc.hip", "ts_gemm_bf16.hip", "ts_attn_bf16.hip"]
+SOURCES = ["ts_host.hip", "ts_kernels_misc.hip", "ts_gemm_bf16.hip", "ts_attn_bf16.hip", "ts_draft.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # keep hipcc from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -39,11 +39,16 @@ def _run(cmd):
 def build_library(verbose=True):
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = _hipcc()
-    objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
 
     def compile_one(pair):
         src, obj = pair
-        out = _run([hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj])
+        inc = ["-I", os.path.join(os.path.dirname(HERE), "include")]
+        if src.endswith(".cpp"):                       # host-only C++ (drafting): no device pass
+            cmd = [hipcc, "-x", "c++", "-O2", "-std=c++17", "-fPIC"] + inc
+        else:
+            cmd = [hipcc] + FLAGS + inc
+        out = _run(cmd + ["-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)
         return obj

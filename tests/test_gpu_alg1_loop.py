@@ -1,0 +1,86 @@
+"""The whole decoding loop of the method (paper Alg. 1) on a small model: host drafter
+(suffix match over retrieved calls, else schema FSM drafts, packed as a tree) -> ts_verify ->
+ts_kv_commit -> FSM update, after a real ts_prefill of the prompt.  The emitted stream must be
+the plain greedy stream of the target (lossless, Sec. 5.1), in fewer target passes than tokens."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import dense_causal as D
+from oracle import drafting_oracle as DO
+from paper_2604_13519_amd import binding as B
+
+import gpu_utils as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("cfg_name", ["small_fp32", "small_bf16"])
+def test_alg1_loop_is_lossless_and_accelerates(cfg_name):
+    cfg, w, model, omodel = U.get_model(cfg_name)
+    n_new = 64
+    # near-ties (top-2 margin below the exemption threshold) may legitimately resolve either way and are
+    # frequent on random-init models: pick a prompt whose greedy stream has none for a while.  The fp32
+    # path differs from the oracle by ~1e-6, so a much smaller threshold is safe there.
+    thresh = 1e-3 if cfg.dtype == wl.configs.DTYPE_F32 else U.MARGIN
+    best = None
+    for seed in range(12):
+        rng = np.random.default_rng([2024, seed])
+        prompt = rng.integers(cfg.vocab, size=120).astype(np.int32)
+        g = D.greedy_sequence(cfg, w, prompt, n_new)        # what the target generates on its own
+        logits = D.causal_forward(cfg, w, np.concatenate([prompt, np.asarray(g[:-1], np.int32)]))
+        top2 = np.sort(np.asarray(logits)[len(prompt) - 1:], axis=1)[:, -2:]
+        safe = next((i for i in range(n_new) if top2[i, 1] - top2[i, 0] < thresh), n_new)
+        if best is None or safe > best[0]:
+            best = (safe, rng, prompt, g)
+        if safe >= 56:
+            break
+    safe, rng, prompt, g = best
+    if safe < 40:
+        pytest.skip("no prompt among 12 whose greedy stream is free of near-ties for 40 tokens")
+    # a schema the target's own output follows for a while: <call> prefix name suffix "param": value ...
+    rnd = lambda n: [int(t) for t in rng.integers(cfg.vocab, size=n)]
+    schema = {"call_open": g[2:3], "name_prefix": g[3:5], "name_suffix": g[7:9], "param_prefix": g[9:10],
+              "param_suffix": g[11:12], "value_end": g[15:16], "call_close": rnd(2),
+              "tools": [rnd(2), g[5:7], rnd(3)], "params": [[rnd(1)], [rnd(2), g[10:11]], []]}
+    # historical calls: one shares the tail of this generation (a recurring invocation), the rest is noise
+    calls = [rnd(40), g[18:60], rnd(25)]
+    H = rng.standard_normal((3, 16)).astype(np.float32)
+    h_x = H[1] + 0.01 * rng.standard_normal(16).astype(np.float32)
+
+    d = B.ts_drafter_create(schema)
+    kv = B.ts_kv_alloc(model, len(prompt) + n_new + 80)
+    try:
+        assert B.ts_drafter_retrieve(d, h_x, H, calls, k=10)[0] == 1
+        B.ts_drafter_reset(d)
+        B.ts_prefill(model, kv, prompt)
+        out, passes, sources, states = [], 0, set(), set()
+        while len(out) < n_new:
+            toks, par, src = B.ts_drafter_draft(d)
+            # the oracle drafter, recomputing everything from the output so far, proposes the same tree
+            otoks, opar, osrc = DO.draft(schema, _ranked(calls, H, h_x), out)
+            assert toks.tolist() == otoks and par.tolist() == opar and src == osrc
+            l, acc, _, bonus = B.ts_verify(model, kv, toks, par)
+            B.ts_kv_commit(kv)
+            emitted = acc + [bonus]
+            B.ts_drafter_append(d, emitted)
+            out += emitted
+            passes += 1
+            sources.add(src)
+            states.add(B.ts_drafter_state(d)[0])
+        assert out[:safe] == g[:safe], "stream %r != greedy %r" % (out[:safe], g[:safe])
+        assert passes < len(out) * 0.6, "%d target passes for %d tokens" % (passes, len(out))
+        assert {B.TS_DRAFT_SCHEMA, B.TS_DRAFT_RETRIEVAL} <= sources
+        # the stream went through the tool-name, parameter-name and value states (token by token, by the
+        # oracle's replay; `states` only samples the step boundaries)
+        assert {1, 2, 3} <= {DO.fsm_replay(schema, out[:i])[0] for i in range(1, len(out) + 1)}
+        assert states <= {0, 1, 2, 3}
+        U._stat("%s Alg. 1 loop: %d tokens in %d target passes" % (cfg_name, len(out), passes))
+    finally:
+        B.ts_kv_free(kv)
+        B.ts_drafter_free(d)
+
+
+def _ranked(calls, H, h_x):
+    order, _ = DO.topk_cosine(h_x, H, 10)
+    return [calls[j] for j in order]
