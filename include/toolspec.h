@@ -116,6 +116,13 @@ ts_status ts_model_keep_logits(ts_model* m, int32_t enable);
  * host_logits: n_rows * vocab floats.  STATE if logits were not kept. */
 ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, float* host_logits);
 
+/* Final normalised hidden state (the input of the lm_head) of one row of the most recent
+ * verify, d_model floats: for row 0 after ingesting a question this is the last-token
+ * representation h_x that retrieval compares with the datastore (Sec. 4.3, Eq. 3).  bf16
+ * models hold it as a (hi, lo) pair of bf16 values; their exact sum is returned.  STATE if
+ * the row is outside the last verify. */
+ts_status ts_get_hidden(ts_model* m, int32_t row, float* host_hidden);
+
 /* ---- KV cache ---------------------------------------------------------------
  * One sequence's cache (the K/V of context x and generated output y): pages of
  * page_size (= 16) positions, addressed through a page table.  capacity_tokens

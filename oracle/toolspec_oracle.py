@@ -196,10 +196,12 @@ def tree_rows(root_token, draft_tokens, parent_idx):
 # --------------------------------------------------------------------------- #
 # the single forward pass with the tree mask (App. A.1)
 # --------------------------------------------------------------------------- #
-def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None):
+def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None, return_hidden=False):
     """Scores all rows in one pass.  Returns (logits[M][V], newK, newV) with
     newK/newV [L][M][Hkv][hd] = the K/V rows of the pass (row r belongs at
-    slot P + r until commit).  Does not modify `kv`."""
+    slot P + r until commit).  Does not modify `kv`.  With return_hidden also the
+    final normalised hidden state [M][d] the logits were computed from (the last-token
+    representation h_x of Sec. 4.3 when the row is a question's last token)."""
     cfg = model.cfg
     rounding = mode == "R" and cfg.dtype == DTYPE_BF16
     rb = bf16_round if rounding else (lambda a: a)               # single bf16 value
@@ -259,6 +261,8 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None):
 
     Xf = rb2(rmsnorm(X, model.tensor("norm_f"), cfg.rms_eps))
     logits = Xf @ model.tensor("lm_head").T
+    if return_hidden:
+        return logits, newK, newV, Xf
     return logits, newK, newV
 
 

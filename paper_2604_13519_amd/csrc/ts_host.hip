@@ -719,6 +719,33 @@ extern "C" ts_status ts_verify_batch(ts_model* m, ts_kv* const* kvs, int32_t n_s
 }
 
 // ---------------------------------------------------------------------------------
+// final hidden state of a row of the most recent verify (query representation for retrieval)
+// ---------------------------------------------------------------------------------
+extern "C" ts_status ts_get_hidden(ts_model* m, int32_t row, float* host_hidden) {
+  if (!m || !host_hidden) return ts_fail(TS_ERR_INVALID_ARG, "ts_get_hidden: null argument");
+  if (row < 0 || row >= m->last_rows) return ts_fail(TS_ERR_STATE, "row %d outside the %d rows of the last verify", row, m->last_rows);
+  (void)hipSetDevice(m->device);
+  const int d = m->cfg.d_model;
+  if (m->cfg.dtype == TS_DTYPE_F32) {
+    TS_HIP(copy_sync(m->stream, host_hidden, (const float*)m->Xn + (size_t)row * d, (size_t)d * 4, hipMemcpyDeviceToHost));
+    return TS_OK;
+  }
+  // bf16 models keep the normalised activations as (hi, lo) bf16 planes: x = hi + lo, exactly representable in fp32
+  std::vector<uint16_t> hi(d), lo(d);
+  const bf16_t* base = (const bf16_t*)m->Xn;
+  TS_HIP(copy_sync(m->stream, hi.data(), base + (size_t)row * d, (size_t)d * 2, hipMemcpyDeviceToHost));
+  TS_HIP(copy_sync(m->stream, lo.data(), base + act_plane(m, d) + (size_t)row * d, (size_t)d * 2, hipMemcpyDeviceToHost));
+  for (int i = 0; i < d; ++i) {
+    uint32_t a = (uint32_t)hi[i] << 16, b = (uint32_t)lo[i] << 16;
+    float fa, fb;
+    memcpy(&fa, &a, 4);
+    memcpy(&fb, &b, 4);
+    host_hidden[i] = fa + fb;
+  }
+  return TS_OK;
+}
+
+// ---------------------------------------------------------------------------------
 // context ingestion through the same kernels: causal chains of up to 65 rows, every row kept
 // ---------------------------------------------------------------------------------
 extern "C" ts_status ts_prefill(ts_model* m, ts_kv* kv, const int32_t* tokens, int32_t n_tokens) {

@@ -118,3 +118,34 @@ def test_prefill_error_paths_leave_state_untouched():
         assert l == 0 and 0 <= bonus < cfg.vocab
     finally:
         B.ts_kv_free(kv)
+
+
+@pytest.mark.parametrize("cfg_name", ["small_fp32", "small_bf16"])
+def test_last_token_hidden_state_for_retrieval(cfg_name):
+    """h_x of Sec. 4.3: the final hidden state at the question's last token = row 0 of the first pass
+    after the question was ingested; also every other row of a tree pass."""
+    cfg, w, model, omodel = U.get_model(cfg_name)
+    fp32 = cfg.dtype == wl.configs.DTYPE_F32
+    rng = np.random.default_rng(31)
+    prompt = rng.integers(cfg.vocab, size=90).astype(np.int32)
+    kv = B.ts_kv_alloc(model, 200)
+    try:
+        with pytest.raises(B.TsError):
+            B.ts_prefill(model, kv, prompt)
+            B.ts_get_hidden(model, 0, cfg.d_model)            # no verify yet: nothing to export
+        okv = O.OracleKV(cfg, 200)
+        mode = "E" if fp32 else "R"
+        _oracle_ingest(cfg, omodel, okv, prompt, mode)
+        tok, par = wl.bfs_tree([], 20, cfg.vocab, rng)
+        B.ts_verify(model, kv, tok, par)
+        rows = O.tree_rows(okv.pending, tok, par)
+        _, _, _, hid = O.forward_tree(omodel, okv, rows[0], rows[2], rows[3], mode, return_hidden=True)
+        tol = 1e-5 if fp32 else 1e-2
+        errs = [U.rel_l2(B.ts_get_hidden(model, r, cfg.d_model), hid[r]) for r in range(len(tok) + 1)]
+        U._stat("%s hidden-state export: max rel L2 %.3g" % (cfg_name, max(errs)))
+        assert max(errs) <= tol
+        with pytest.raises(B.TsError) as e:
+            B.ts_get_hidden(model, len(tok) + 1, cfg.d_model)
+        assert e.value.status == B.TS_ERR_STATE
+    finally:
+        B.ts_kv_free(kv)
