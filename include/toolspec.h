@@ -169,6 +169,24 @@ ts_status ts_verify(ts_model* m, ts_kv* kv,
                     int32_t* accept_len, int32_t* accepted_tokens, int32_t* accepted_nodes,
                     int32_t* bonus_token);
 
+/* Stochastic acceptance (the paper's stated acceptance strategy, App. B.2: speculative sampling,
+ * Leviathan et al. 2023), for one sequence.  Same pass and same outputs as ts_verify, but at a row
+ * with target distribution p = softmax(logits / temperature) the children are tried in node order:
+ * child c with token x is accepted with probability p(x) / (1 - mass of its siblings rejected
+ * before it), decided by node_uniform[c] < that ratio; a rejected token leaves the distribution; a
+ * sibling repeating a rejected token is rejected.  When every child of a row is rejected (or it
+ * has none) the step ends with a sample of what is left of p there: bonus_token = arg-max over the
+ * remaining tokens of logits / temperature + Gumbel noise, noise(row, token) = -log(-log(u)),
+ * u = (top 23 bits of splitmix64(noise_seed + (row << 32 | token)) + 0.5) / 2^23.  The emitted
+ * tokens are distributed as the target model's own samples.
+ *   node_uniform : n_nodes floats in [0,1), the caller's random draws (one per draft node)
+ * Errors as ts_verify, plus INVALID_ARG for temperature <= 0 or a uniform outside [0,1). */
+ts_status ts_verify_sample(ts_model* m, ts_kv* kv,
+                           const int32_t* draft_tokens, const int32_t* parent_idx, int32_t n_nodes,
+                           float temperature, const float* node_uniform, uint64_t noise_seed,
+                           int32_t* accept_len, int32_t* accepted_tokens, int32_t* accepted_nodes,
+                           int32_t* bonus_token);
+
 /* Same for n_seqs independent sequences in one pass (weights are streamed once).
  * Nodes are concatenated; node_offsets has n_seqs + 1 entries; parent indices are
  * local to their sequence.  accepted_tokens / accepted_nodes use the same offsets.

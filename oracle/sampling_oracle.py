@@ -32,14 +32,15 @@ def splitmix64(state):
 
 
 def gumbel_noise(seed, row, n_vocab):
-    """Gumbel(0,1) noise of one row: u = (top 24 bits + 0.5) / 2^24, g = -log(-log u)."""
+    """Gumbel(0,1) noise of one row: u = (top 23 bits + 0.5) / 2^23 (exact in single precision as
+    well), g = -log(-log u)."""
     v = np.arange(n_vocab, dtype=np.uint64)
     s = (np.uint64(seed & _M64) + ((np.uint64(row) << np.uint64(32)) | v))
     z = s + np.uint64(0x9E3779B97F4A7C15)
     z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
     z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
     z = z ^ (z >> np.uint64(31))
-    u = ((z >> np.uint64(40)).astype(np.float64) + 0.5) / float(1 << 24)
+    u = ((z >> np.uint64(41)).astype(np.float64) + 0.5) / float(1 << 23)
     return -np.log(-np.log(u))
 
 

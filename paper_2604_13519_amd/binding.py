@@ -22,7 +22,7 @@ TS_DRAFT_NONE, TS_DRAFT_RETRIEVAL, TS_DRAFT_SCHEMA = 0, 1, 2
 
 EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits", "ts_get_hidden",
            "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export",
-           "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_batch",
+           "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_sample", "ts_verify_batch",
            "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read",
            "ts_drafter_create", "ts_drafter_free", "ts_drafter_retrieve", "ts_drafter_reset",
            "ts_drafter_append", "ts_drafter_state", "ts_drafter_draft")
@@ -97,6 +97,8 @@ def load_library(path=None):
         "ts_kv_truncate": [C.c_void_p, C.c_int32],
         "ts_prefill": [C.c_void_p, C.c_void_p, i32p, C.c_int32],
         "ts_verify": [C.c_void_p, C.c_void_p, i32p, i32p, C.c_int32, i32p, i32p, i32p, i32p],
+        "ts_verify_sample": [C.c_void_p, C.c_void_p, i32p, i32p, C.c_int32, C.c_float, C.POINTER(C.c_float), C.c_uint64,
+                             i32p, i32p, i32p, i32p],
         "ts_verify_batch": [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, i32p, i32p, i32p, i32p, i32p, i32p, i32p],
         "ts_kv_commit": [C.c_void_p],
         "ts_profile_enable": [C.c_void_p, C.c_int32],
@@ -250,6 +252,23 @@ def ts_verify(model, kv, draft_tokens, parent_idx):
     nodes = np.zeros(max(n, 1), np.int32)
     _check(load_library().ts_verify(model, kv, _ptr_i32(t), _ptr_i32(p), n, C.byref(acc_len),
                                     _ptr_i32(toks), _ptr_i32(nodes), C.byref(bonus)))
+    l = acc_len.value
+    return l, toks[:l].tolist(), nodes[:l].tolist(), bonus.value
+
+
+def ts_verify_sample(model, kv, draft_tokens, parent_idx, temperature, node_uniform, noise_seed):
+    """Stochastic acceptance; returns (accept_len, accepted_tokens, accepted_nodes, bonus_token)."""
+    t, p = _i32(draft_tokens), _i32(parent_idx)
+    u = np.ascontiguousarray(node_uniform, dtype=np.float32)
+    n = len(t)
+    if len(p) != n or len(u) != n:
+        raise ValueError("draft_tokens, parent_idx and node_uniform differ in length")
+    acc_len, bonus = C.c_int32(), C.c_int32()
+    toks = np.zeros(max(n, 1), np.int32)
+    nodes = np.zeros(max(n, 1), np.int32)
+    _check(load_library().ts_verify_sample(model, kv, _ptr_i32(t), _ptr_i32(p), n, float(temperature),
+                                           u.ctypes.data_as(C.POINTER(C.c_float)), int(noise_seed) & ((1 << 64) - 1),
+                                           C.byref(acc_len), _ptr_i32(toks), _ptr_i32(nodes), C.byref(bonus)))
     l = acc_len.value
     return l, toks[:l].tolist(), nodes[:l].tolist(), bonus.value
 

@@ -117,19 +117,21 @@ static void free_workspace(ts_model* m) {
   dev_free(m->H); dev_free(m->Xn); dev_free(m->Qb); dev_free(m->Ab); dev_free(m->Fb); dev_free(m->part);
   dev_free(m->attn_part_o); dev_free(m->attn_part_ml); dev_free(m->rope_cs); dev_free(m->amax_val);
   dev_free(m->amax_idx); dev_free(m->logits); dev_free(m->meta_dev); dev_free(m->seq_dev);
+  dev_free(m->samp_lse); dev_free(m->samp_tok);
   if (m->meta_host) (void)hipHostFree(m->meta_host);
   if (m->res_host) (void)hipHostFree(m->res_host);
   m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr;
   m->attn_part_o = m->attn_part_ml = nullptr; m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr;
   m->logits = nullptr; m->meta_dev = nullptr; m->seq_dev = nullptr; m->meta_host = nullptr; m->res_host = nullptr;
+  m->samp_lse = nullptr; m->samp_tok = nullptr;
   m->ws_rows = 0; m->ws_seqs = 0; m->logits_rows = 0; m->attn_max_splits = 0;
 }
 
-static size_t meta_bytes_for(int rows) { return (size_t)rows * (6 * sizeof(int32_t) + sizeof(uint64_t)); }
+static size_t meta_bytes_for(int rows) { return (size_t)rows * (6 * sizeof(int32_t) + sizeof(uint64_t) + sizeof(float)); }
 
 // Row buffers carry TS_MROWS_PER_BLOCK spare rows: tile-granular kernels read (never use)
 // rows past the last real one.
-static ts_status ensure_workspace(ts_model* m, int rows, int seqs) {
+static ts_status ensure_workspace(ts_model* m, int rows, int seqs, bool want_logits = false) {
   const ts_model_config& c = m->cfg;
   ts_status st;
   if (rows > m->ws_rows || seqs > m->ws_seqs) {
@@ -164,6 +166,8 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs) {
     if ((st = dev_alloc_bytes((void**)&m->rope_cs, (size_t)alloc_rows * (c.head_dim / 2) * sizeof(float2), true))) return st;
     if ((st = dev_alloc_bytes((void**)&m->amax_val, (size_t)alloc_rows * m->amax_parts * 4, true))) return st;
     if ((st = dev_alloc_bytes((void**)&m->amax_idx, (size_t)alloc_rows * m->amax_parts * 4, true))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->samp_lse, (size_t)alloc_rows * 4, true))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->samp_tok, (size_t)alloc_rows * 4, true))) return st;
     m->meta_bytes = meta_bytes_for(alloc_rows);
     if ((st = dev_alloc_bytes(&m->meta_dev, m->meta_bytes, true))) return st;
     if ((st = dev_alloc_bytes((void**)&m->seq_dev, (size_t)scap * sizeof(SeqDesc), true))) return st;
@@ -173,7 +177,7 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs) {
     m->ws_seqs = scap;
     m->keep_logits = keep;
   }
-  const bool need_logits = m->keep_logits || c.dtype == TS_DTYPE_F32;
+  const bool need_logits = m->keep_logits || want_logits || c.dtype == TS_DTYPE_F32;
   if (need_logits && m->logits_rows < m->ws_rows) {
     TS_HIP(hipStreamSynchronize(m->stream));
     dev_free(m->logits);
@@ -333,6 +337,7 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr; m->logits = nullptr;
   m->keep_logits = false; m->logits_rows = 0; m->meta_dev = nullptr; m->meta_host = nullptr; m->meta_bytes = 0;
   m->seq_dev = nullptr; m->res_host = nullptr; m->ws_rows = 0; m->ws_seqs = 0;
+  m->samp_lse = nullptr; m->samp_tok = nullptr;
   m->prof_on = false; m->ev_used = 0; m->last_rows = 0;
   hipError_t e = hipGetDevice(&m->device);
   hipDeviceProp_t prop;
@@ -531,15 +536,19 @@ static RowMeta carve_meta(void* base, int rows) {
   rm.seq = (int32_t*)p;  p += (size_t)rows * 4;
   rm.lrow = (int32_t*)p; p += (size_t)rows * 4;
   rm.par = (int32_t*)p;  p += (size_t)rows * 4;
-  rm.depth = (int32_t*)p;
+  rm.depth = (int32_t*)p; p += (size_t)rows * 4;
+  rm.u = (float*)p;
   return rm;
 }
 
 // ingest_only: run the layers (K/V of every row land in the tree slots) but not the final
 // norm, lm_head, arg-max and walk, and leave no verify result behind (context ingestion).
+// sample: stochastic acceptance instead of the greedy walk (one sequence; logits are materialised).
+struct SampleArgs { float temperature; const float* node_uniform; uint64_t seed; };
+
 static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const int32_t* toks, const int32_t* pars,
                              const int32_t* offs, int32_t* accept_len, int32_t* acc_tokens, int32_t* acc_nodes,
-                             int32_t* bonus, bool ingest_only = false) {
+                             int32_t* bonus, bool ingest_only = false, const SampleArgs* sample = nullptr) {
   const ts_model_config& c = m->cfg;
   const bool bf = c.dtype == TS_DTYPE_BF16;
   // ---- validation (nothing is modified before it passes) ---------------------------
@@ -569,7 +578,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     return ts_fail(TS_ERR_KV_CAPACITY, "fp32 path supports at most %zu keys per sequence", attn_f32_max_keys());
 
   (void)hipSetDevice(m->device);
-  ts_status st = ensure_workspace(m, R, n_seqs);
+  ts_status st = ensure_workspace(m, R, n_seqs, sample != nullptr);
   if (st) return st;
   const int splits = bf ? attn_bf16_splits(m, max_keys, n_seqs) : 1;
   if ((st = ensure_attn_partials(m, splits, R))) return st;
@@ -584,7 +593,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     ts_kv* kv = kvs[s];
     const int n = offs[s + 1] - offs[s];
     hm.tok[r0] = kv->pending; hm.pos[r0] = kv->P; hm.seq[r0] = s; hm.lrow[r0] = 0;
-    hm.par[r0] = -1; hm.depth[r0] = 0; hm.anc[r0] = 0;
+    hm.par[r0] = -1; hm.depth[r0] = 0; hm.anc[r0] = 0; hm.u[r0] = 0.f;
     for (int i = 0; i < n; ++i) {
       const int r = r0 + i + 1;
       const int prow = pars[offs[s] + i] + 1;             // local parent row
@@ -593,6 +602,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
       hm.depth[r] = hm.depth[r0 + prow] + 1;
       hm.pos[r] = kv->P + hm.depth[r];
       hm.anc[r] = hm.anc[r0 + prow] | (1ull << i);
+      hm.u[r] = sample ? sample->node_uniform[offs[s] + i] : 0.f;
     }
     SeqDesc& sd = hseq[s];
     sd.P = kv->P; sd.M = n + 1; sd.row0 = r0; sd.n_pages = kv->n_pages;
@@ -660,12 +670,13 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     const GemmPlan p = gemm_bf16_plan(m, TS_MROWS_PER_BLOCK, c.vocab, d, 1);   // as at load: fixes the partial count
     ProfScope ps(m, "gemm_lm_head_argmax");
     launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)m->lm_head, nullptr, R, c.vocab, d, p, 1,
-                     m->keep_logits ? m->logits : nullptr, nullptr);
+                     (m->keep_logits || sample) ? m->logits : nullptr, nullptr);
   } else {
     launch_gemm_f32(m, (const float*)m->Xn, (const float*)m->lm_head, m->logits, R, c.vocab, d);
     launch_argmax_rows(m, R);
   }
-  launch_walk(m, dm, n_seqs);
+  if (sample) launch_sample(m, dm, R, n_seqs, sample->temperature, sample->seed);
+  else launch_walk(m, dm, n_seqs);
   TS_HIP(hipGetLastError());
   for (int s = 0; s < n_seqs; ++s)
     TS_HIP(hipMemcpyAsync(m->res_host + (size_t)s * TS_RESULT_INTS, kvs[s]->result, TS_RESULT_INTS * 4, hipMemcpyDeviceToHost, m->stream));
@@ -704,6 +715,23 @@ extern "C" ts_status ts_verify(ts_model* m, ts_kv* kv, const int32_t* draft_toke
   const int32_t offs[2] = {0, n_nodes};
   ts_kv* kvs[1] = {kv};
   return verify_impl(m, kvs, 1, draft_tokens, parent_idx, offs, accept_len, accepted_tokens, accepted_nodes, bonus_token);
+}
+
+extern "C" ts_status ts_verify_sample(ts_model* m, ts_kv* kv, const int32_t* draft_tokens, const int32_t* parent_idx,
+                                      int32_t n_nodes, float temperature, const float* node_uniform, uint64_t noise_seed,
+                                      int32_t* accept_len, int32_t* accepted_tokens, int32_t* accepted_nodes,
+                                      int32_t* bonus_token) {
+  if (!m || !kv || !accept_len || !bonus_token || (n_nodes > 0 && (!accepted_tokens || !node_uniform)))
+    return ts_fail(TS_ERR_INVALID_ARG, "ts_verify_sample: null argument");
+  if (n_nodes < 0 || n_nodes > TS_MAX_NODES) return ts_fail(TS_ERR_INVALID_TREE, "n_nodes %d outside [0,%d]", n_nodes, TS_MAX_NODES);
+  if (!(temperature > 0.f) || !(temperature < 1e6f)) return ts_fail(TS_ERR_INVALID_ARG, "temperature %g must be positive and finite", temperature);
+  for (int i = 0; i < n_nodes; ++i)
+    if (!(node_uniform[i] >= 0.f && node_uniform[i] < 1.f))
+      return ts_fail(TS_ERR_INVALID_ARG, "node_uniform[%d] = %g outside [0,1)", i, node_uniform[i]);
+  const int32_t offs[2] = {0, n_nodes};
+  ts_kv* kvs[1] = {kv};
+  const SampleArgs sa{temperature, node_uniform, noise_seed};
+  return verify_impl(m, kvs, 1, draft_tokens, parent_idx, offs, accept_len, accepted_tokens, accepted_nodes, bonus_token, false, &sa);
 }
 
 extern "C" ts_status ts_verify_batch(ts_model* m, ts_kv* const* kvs, int32_t n_seqs, const int32_t* draft_tokens,

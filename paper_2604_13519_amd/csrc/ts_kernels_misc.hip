@@ -369,6 +369,133 @@ void launch_walk(ts_model* m, const RowMeta& rm, int n_seqs) {
 }
 
 // ---------------------------------------------------------------------------------
+// Stochastic acceptance (speculative sampling with point-mass drafts; App. B.2 names the
+// rule, Leviathan et al. 2023).  Two kernels over the materialised logits of one sequence:
+//  k_sample_rows  per row: log-sum-exp of logits / T, and the residual sample the step would
+//                 end with at this row: arg-max of logits / T + Gumbel noise over all tokens
+//                 except those of the row's children (if the walk stops here, every child was
+//                 rejected and its token removed from the distribution).
+//  k_walk_sample  child c of row r is accepted with probability p_r(x_c) / (1 - mass of the
+//                 siblings rejected before it), decided by the caller's uniform of that node.
+// Noise: one splitmix64 output per (seed, row within the sequence, token); its top 23 bits
+// (+ 0.5) / 2^23 are the uniform, exact in single precision.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float gumbel_noise(uint64_t seed, int lrow, int v) {
+  uint64_t z = seed + (((uint64_t)(uint32_t)lrow << 32) | (uint32_t)v) + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z = z ^ (z >> 31);
+  const float u = ((float)(uint32_t)(z >> 41) + 0.5f) * (1.0f / 8388608.0f);
+  return -logf(-logf(u));
+}
+
+__global__ __launch_bounds__(1024) void k_sample_rows(const float* __restrict__ logits, int V, float inv_t, uint64_t seed,
+                                                      const int32_t* __restrict__ tok, const int32_t* __restrict__ par,
+                                                      const int32_t* __restrict__ lrow, const int32_t* __restrict__ row_seq,
+                                                      const SeqDesc* __restrict__ seqs, float* __restrict__ lse,
+                                                      int32_t* __restrict__ samp_tok) {
+  __shared__ int excl[TS_MAX_NODES + 1];
+  __shared__ int n_excl;
+  __shared__ float sm[16], ss[16], sv[16];
+  __shared__ int si[16];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const SeqDesc sd = seqs[row_seq[row]];
+  const int lr = lrow[row];
+  if (tid == 0) n_excl = 0;
+  __syncthreads();
+  if (tid < sd.M && tid > 0 && par[sd.row0 + tid] == lr) excl[atomicAdd(&n_excl, 1)] = tok[sd.row0 + tid];
+  __syncthreads();
+  const int ne = n_excl;
+  const float* p = logits + (size_t)row * V;
+  float m = -INFINITY, s = 0.f, bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int v = tid; v < V; v += 1024) {
+    const float z = p[v] * inv_t;
+    if (z > m) { s = s * expf(m - z) + 1.0f; m = z; } else { s += expf(z - m); }
+    bool ex = false;
+    for (int e = 0; e < ne; ++e) ex |= (excl[e] == v);
+    if (!ex) amax_take(bv, bi, z + gumbel_noise(seed, lr, v), v);
+  }
+  // combine (max, sum of exponentials) and the best perturbed score over the wave, then over the block
+  for (int o = 32; o > 0; o >>= 1) {
+    const float om = __shfl_xor(m, o, 64), os = __shfl_xor(s, o, 64);
+    const float mm = fmaxf(m, om);
+    s = (m == -INFINITY ? 0.f : s * expf(m - mm)) + (om == -INFINITY ? 0.f : os * expf(om - mm));
+    m = mm;
+  }
+  wave_amax(bv, bi);
+  if ((tid & 63) == 0) { sm[tid >> 6] = m; ss[tid >> 6] = s; sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 16; ++w) {
+      const float mm = fmaxf(m, sm[w]);
+      s = (m == -INFINITY ? 0.f : s * expf(m - mm)) + (sm[w] == -INFINITY ? 0.f : ss[w] * expf(sm[w] - mm));
+      m = mm;
+      amax_take(bv, bi, sv[w], si[w]);
+    }
+    lse[row] = m + logf(s);
+    samp_tok[row] = bi;
+  }
+}
+
+__global__ __launch_bounds__(128) void k_walk_sample(const float* __restrict__ logits, int V, float inv_t,
+                                                     const float* __restrict__ lse, const int32_t* __restrict__ samp_tok,
+                                                     const float* __restrict__ node_u, const int32_t* __restrict__ tok,
+                                                     const int32_t* __restrict__ par, const SeqDesc* __restrict__ seqs) {
+  __shared__ float prob[TS_MAX_NODES + 1], uu[TS_MAX_NODES + 1];
+  __shared__ int s_tok[TS_MAX_NODES + 1], s_par[TS_MAX_NODES + 1];
+  const SeqDesc sd = seqs[blockIdx.x];
+  const int t = threadIdx.x;
+  if (t < sd.M) {
+    s_tok[t] = tok[sd.row0 + t];
+    s_par[t] = par[sd.row0 + t];
+    if (t > 0) {                       // probability of this node's token under its parent's distribution
+      const int pr = sd.row0 + s_par[t];
+      prob[t] = expf(logits[(size_t)pr * V + s_tok[t]] * inv_t - lse[pr]);
+      uu[t] = node_u[sd.row0 + t];
+    }
+  }
+  __syncthreads();
+  if (t != 0) return;
+  int32_t* res = sd.result;
+  int r = 0, len = 0;
+  for (;;) {
+    float rem = 1.0f;
+    int rejected[TS_MAX_NODES];
+    int n_rej = 0, nxt = -1;
+    for (int c = 1; c < sd.M && nxt < 0; ++c) {
+      if (s_par[c] != r) continue;
+      bool dup = false;
+      for (int e = 0; e < n_rej; ++e) dup |= (rejected[e] == s_tok[c]);
+      if (dup) continue;               // its token was already removed from the distribution
+      if (uu[c] < prob[c] / rem) {
+        nxt = c;
+      } else {
+        rejected[n_rej++] = s_tok[c];
+        rem -= prob[c];
+      }
+    }
+    if (nxt < 0) break;
+    res[4 + len] = nxt;
+    res[4 + TS_MAX_NODES + len] = s_tok[nxt];
+    ++len;
+    r = nxt;
+  }
+  res[0] = len;
+  res[1] = samp_tok[sd.row0 + r];
+  res[2] = r;
+}
+
+void launch_sample(ts_model* m, const RowMeta& rm, int R, int n_seqs, float temperature, uint64_t seed) {
+  ProfScope ps(m, "sample_accept");
+  const float inv_t = 1.0f / temperature;
+  hipLaunchKernelGGL(k_sample_rows, dim3(R), dim3(1024), 0, m->stream, m->logits, m->cfg.vocab, inv_t, seed, rm.tok, rm.par,
+                     rm.lrow, rm.seq, m->seq_dev, m->samp_lse, m->samp_tok);
+  hipLaunchKernelGGL(k_walk_sample, dim3(n_seqs), dim3(128), 0, m->stream, m->logits, m->cfg.vocab, inv_t, m->samp_lse,
+                     m->samp_tok, rm.u, rm.tok, rm.par, m->seq_dev);
+}
+
+// ---------------------------------------------------------------------------------
 // commit: move the K/V of the accepted row of depth d from tree slot P + row_d to slot
 // P + d, for d = 1..l.  A thread owns one element column (one head-dim index of one KV
 // head of one layer) across all depths and walks d upwards; since row_d >= d and rows

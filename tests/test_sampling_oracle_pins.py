@@ -17,7 +17,7 @@ def test_splitmix64_known_answers():
     gn = SO.gumbel_noise(seed, row, 5)
     for v in range(5):
         z = SO.splitmix64((seed + ((row << 32) | v)) & ((1 << 64) - 1))
-        u = ((z >> 40) + 0.5) / (1 << 24)
+        u = ((z >> 41) + 0.5) / (1 << 23)
         assert abs(gn[v] - (-np.log(-np.log(u)))) < 1e-12
 
 
