@@ -29,8 +29,6 @@
 // probabilities 2^(s - ref) are rounded to half for the second product and the row sum
 // accumulates those rounded values (an extra MFMA against an all-ones operand, fp32 exact).
 // Partial (max, sum, O) per split are combined by k_attn_merge.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "ts_internal.h"
@@ -421,14 +419,8 @@ void launch_hd(int hb, int tiles, dim3 grid, hipStream_t s, const AttnArgs& a) {
   else launch_hb<HD, 1>(tiles, grid, s, a);
 }
 
-// two heads per workgroup: 4 waves of 256 registers, so two workgroups share a CU and one's
-// waits on K/V loads are covered by the other's arithmetic
-int heads_per_block(int G) {
-  static const int pref = getenv("TS_ATTN_HB") ? atoi(getenv("TS_ATTN_HB")) : 4;   // tuning knob
-  int hb = G >= 4 ? 4 : (G >= 2 ? 2 : 1);
-  if (pref == 2 && hb > 2) hb = 2;
-  return hb;
-}
+// query heads of one KV head served by a workgroup (one wave each per row split)
+int heads_per_block(int G) { return G >= 4 ? 4 : (G >= 2 ? 2 : 1); }
 
 }  // namespace
 
@@ -441,10 +433,6 @@ int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs) {
   int want = (wg_per_cu * m->n_cu + per_split - 1) / per_split;
   if (want < 1) want = 1;
   if (want > n_blk) want = n_blk;
-  if (const char* e = getenv("TS_ATTN_MAX_SPLITS")) {   // tuning / debugging knob
-    const int cap = atoi(e);
-    if (cap >= 1 && want > cap) want = cap;
-  }
   if (want > kMergeMaxSplits) want = kMergeMaxSplits;      // the merge kernel keeps (max, sum) of every split in LDS
   const int bps = (n_blk + want - 1) / want;
   return (n_blk + bps - 1) / bps;

@@ -306,19 +306,16 @@ void launch_mt(int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
 }
 
 // The compiled tile shapes.  shape id -> (NT, CS, KW): tiles per wave, column sets and
-// k-waves per workgroup.  Shape 5 (96 columns, 6 waves) exists because 6144 output features
-// (the 8B QKV projection) fill 256 CUs as 64 groups x 4 splits but only 192 as 48 x 4.  All use chunks of 128 k (the LDS holds two buffers of two planes of
+// k-waves per workgroup.  All use chunks of 128 k (the LDS holds two buffers of two planes of
 // the activation chunk, 85 KiB for 80 rows).  The k-wave shapes hold fewer weight registers
-// per chunk and prefetch several chunks ahead instead.
-#ifdef TS_GEMM_EXPERIMENT
-constexpr int kNumShapes = 8;
-#else
+// per chunk and prefetch two chunks ahead instead of one.  Shape 5 (96 columns, 6 waves) exists
+// because 6144 output features (the 8B QKV projection) fill 256 CUs as 64 groups x 4 splits
+// but only 192 as 48 x 4.
 constexpr int kNumShapes = 6;
-#endif
-const int kShapeNT[8] = {1, 2, 1, 2, 2, 2, 2, 2};
-const int kShapeCS[8] = {4, 4, 8, 8, 4, 3, 4, 4};
-const int kShapeKW[8] = {1, 1, 1, 1, 2, 2, 2, 2};
-const int kShapeKC[8] = {128, 128, 128, 128, 128, 128, 128, 64};
+const int kShapeNT[kNumShapes] = {1, 2, 1, 2, 2, 2};
+const int kShapeCS[kNumShapes] = {4, 4, 8, 8, 4, 3};
+const int kShapeKW[kNumShapes] = {1, 1, 1, 1, 2, 2};
+const int kShapeKC[kNumShapes] = {128, 128, 128, 128, 128, 128};
 
 template <int MODE>
 void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
@@ -329,10 +326,6 @@ void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a
     case 3: launch_mt<2, 8, 1, 128, 1, MODE>(mt, grid, s, a); break;
     case 4: if (MODE != MODE_ARGMAX) launch_mt<2, 4, 2, 128, 2, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
     case 5: if (MODE != MODE_ARGMAX) launch_mt<2, 3, 2, 128, 2, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
-#ifdef TS_GEMM_EXPERIMENT
-    case 6: if (MODE != MODE_ARGMAX) launch_mt<2, 4, 2, 128, 3, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
-    case 7: if (MODE != MODE_ARGMAX) launch_mt<2, 4, 2, 64, 5, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
-#endif
     default: break;
   }
 }
@@ -360,7 +353,7 @@ GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
   double best_cost = 1e300;
   const int rows = R > TS_MROWS_PER_BLOCK ? TS_MROWS_PER_BLOCK : ((R + 15) / 16) * 16;
   const int m_blocks = (R + TS_MROWS_PER_BLOCK - 1) / TS_MROWS_PER_BLOCK;   // each streams the weights again
-  for (int shape = 0; shape < 6; ++shape) {
+  for (int shape = 0; shape < kNumShapes; ++shape) {
     if (!shape_supports(shape, mode)) continue;
     const int kc = kShapeKC[shape];
     if (K % kc) continue;

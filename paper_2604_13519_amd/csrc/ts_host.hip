@@ -676,7 +676,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     launch_argmax_rows(m, R);
   }
   if (sample) launch_sample(m, dm, R, n_seqs, sample->temperature, sample->seed);
-  else launch_walk(m, dm, n_seqs);
+  else launch_walk(m, dm, R, n_seqs);
   TS_HIP(hipGetLastError());
   for (int s = 0; s < n_seqs; ++s)
     TS_HIP(hipMemcpyAsync(m->res_host + (size_t)s * TS_RESULT_INTS, kvs[s]->result, TS_RESULT_INTS * 4, hipMemcpyDeviceToHost, m->stream));

@@ -98,7 +98,7 @@ struct ts_model {
   float2* rope_cs;              // [rows][hd/2] (cos, sin)
   float* amax_val; int32_t* amax_idx; int amax_parts;   // [rows][parts]
   float* logits; bool keep_logits; int logits_rows;     // [rows][V] when kept
-  float* samp_lse; int32_t* samp_tok;                   // stochastic acceptance: per-row log-sum-exp and residual sample
+  float* samp_lse; int32_t* samp_tok;                   // per-row token (greedy arg-max or residual sample); log-sum-exp for sampling
   // per-call metadata (device + pinned host mirror)
   void* meta_dev; void* meta_host; size_t meta_bytes;
   SeqDesc* seq_dev;
@@ -121,7 +121,7 @@ void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part
 void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_parts, size_t part_stride);
 void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride);
 void launch_argmax_rows(ts_model* m, int R);
-void launch_walk(ts_model* m, const RowMeta& rm, int n_seqs);
+void launch_walk(ts_model* m, const RowMeta& rm, int R, int n_seqs);
 void launch_sample(ts_model* m, const RowMeta& rm, int R, int n_seqs, float temperature, uint64_t seed);
 void launch_commit(ts_kv* kv, int accept_len);
 void launch_kv_import(ts_kv* kv, int pos0, int n_pos, const void* staged_k, const void* staged_v, int layer);

@@ -297,46 +297,56 @@ void launch_argmax_rows(ts_model* m, int R) {
 }
 
 // ---------------------------------------------------------------------------------
-// greedy acceptance walk, one block (16 waves) per sequence.
-//   g[r]     = arg-max token of row r, combined from `parts` (value, index) partials
+// greedy acceptance, two small kernels.
+//  k_argmax_combine  one block per row: g[row] = arg-max token, combined from the `parts`
+//                    (value, index) partials of the lm_head epilogue (lowest index on ties)
+//  k_walk            one block per sequence:
 //   valid[r] = valid[parent(r)] && tok[r] == g[parent(r)],  valid[root] = true
 //   best     = deepest valid row, lowest row index among equals
 // result: [0] accept_len, [1] bonus token g[best], [2] best row, [4+i] row of depth i+1,
 //         [4+64+i] token of depth i+1.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_walk(const float* __restrict__ aval, const int32_t* __restrict__ aidx, int parts,
-                                               int used_parts, const int32_t* __restrict__ tok,
-                                               const int32_t* __restrict__ par, const int32_t* __restrict__ depth,
-                                               const SeqDesc* __restrict__ seqs) {
+__global__ __launch_bounds__(256) void k_argmax_combine(const float* __restrict__ aval, const int32_t* __restrict__ aidx,
+                                                        int parts, int used_parts, int32_t* __restrict__ g) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const size_t base = (size_t)blockIdx.x * parts;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int p0 = 0; p0 < used_parts; p0 += 256 * 4) {   // 4 independent loads per thread in flight
+    float v4[4];
+    int i4[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = p0 + j * 256 + threadIdx.x;
+      const bool ok = p < used_parts;
+      v4[j] = ok ? aval[base + p] : -INFINITY;
+      i4[j] = ok ? aidx[base + p] : 0x7fffffff;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) amax_take(bv, bi, v4[j], i4[j]);
+  }
+  wave_amax(bv, bi);
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) amax_take(bv, bi, sv[w], si[w]);
+    g[blockIdx.x] = bi;
+  }
+}
+
+__global__ __launch_bounds__(128) void k_walk(const int32_t* __restrict__ g_row, const int32_t* __restrict__ tok,
+                                              const int32_t* __restrict__ par, const int32_t* __restrict__ depth,
+                                              const SeqDesc* __restrict__ seqs) {
   __shared__ int g[TS_MAX_NODES + 1];
   __shared__ int s_tok[TS_MAX_NODES + 1], s_par[TS_MAX_NODES + 1], s_dep[TS_MAX_NODES + 1];
   __shared__ unsigned char valid[TS_MAX_NODES + 1];
   const SeqDesc sd = seqs[blockIdx.x];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (threadIdx.x < sd.M) {                           // the serial walk below reads the tree from LDS
+    g[threadIdx.x] = g_row[sd.row0 + threadIdx.x];
     s_tok[threadIdx.x] = tok[sd.row0 + threadIdx.x];
     s_par[threadIdx.x] = par[sd.row0 + threadIdx.x];
     s_dep[threadIdx.x] = depth[sd.row0 + threadIdx.x];
-  }
-  for (int r = wave; r < sd.M; r += 16) {            // one wave per row, lanes stride over the partials
-    const size_t base = (size_t)(sd.row0 + r) * parts;
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    for (int p0 = 0; p0 < used_parts; p0 += 64 * 8) { // 8 independent loads per lane in flight
-      float v8[8];
-      int i8[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int p = p0 + j * 64 + lane;
-        const bool ok = p < used_parts;
-        v8[j] = ok ? aval[base + p] : -INFINITY;
-        i8[j] = ok ? aidx[base + p] : 0x7fffffff;
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) amax_take(bv, bi, v8[j], i8[j]);
-    }
-    wave_amax(bv, bi);
-    if (lane == 0) g[r] = bi;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -362,10 +372,11 @@ __global__ __launch_bounds__(1024) void k_walk(const float* __restrict__ aval, c
   }
 }
 
-void launch_walk(ts_model* m, const RowMeta& rm, int n_seqs) {
+void launch_walk(ts_model* m, const RowMeta& rm, int R, int n_seqs) {
   ProfScope ps(m, "accept_walk");
-  hipLaunchKernelGGL(k_walk, dim3(n_seqs), dim3(1024), 0, m->stream, m->amax_val, m->amax_idx, m->amax_parts,
-                     m->amax_parts, rm.tok, rm.par, rm.depth, m->seq_dev);
+  hipLaunchKernelGGL(k_argmax_combine, dim3(R), dim3(256), 0, m->stream, m->amax_val, m->amax_idx, m->amax_parts,
+                     m->amax_parts, m->samp_tok);
+  hipLaunchKernelGGL(k_walk, dim3(n_seqs), dim3(128), 0, m->stream, m->samp_tok, rm.tok, rm.par, rm.depth, m->seq_dev);
 }
 
 // ---------------------------------------------------------------------------------
