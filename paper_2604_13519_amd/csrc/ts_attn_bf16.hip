@@ -424,13 +424,23 @@ int heads_per_block(int G) { return G >= 4 ? 4 : (G >= 2 ? 2 : 1); }
 
 }  // namespace
 
-// Number of key splits: enough workgroups to cover the CUs, never more than key blocks.
-int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs) {
+// Number of key splits (every sequence is cut into the same number of splits, each covering
+// ceil(blocks / splits) of ITS key blocks).  One sequence: enough workgroups to cover the CUs
+// once.  Several sequences of different lengths: one round would be as slow as the longest
+// sequence's share, so the splits are made fine enough that the longest workgroup carries at
+// most half of a CU's average load and the dispatcher can even the rest out over a few rounds.
+int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs, long sum_keys) {
   const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
-  const int per_split = m->cfg.n_kv_heads * (G / heads_per_block(G)) * n_seqs;
+  const int subs = G / heads_per_block(G);
+  const int per_split = m->cfg.n_kv_heads * subs * n_seqs;
   const int n_blk = (max_keys + KB - 1) / KB;
   const int wg_per_cu = heads_per_block(G) <= 2 ? 2 : 1;
   int want = (wg_per_cu * m->n_cu + per_split - 1) / per_split;
+  if (n_seqs > 1) {
+    const double avg_per_cu = (double)((sum_keys + KB - 1) / KB) * m->cfg.n_kv_heads * subs / m->n_cu;
+    const int fine = (int)((double)n_blk / (avg_per_cu > 2.0 ? avg_per_cu / 2.0 : 1.0) + 0.999);
+    if (fine > want) want = fine < 16 ? fine : 16;          // partial sums grow with the split count
+  }
   if (want < 1) want = 1;
   if (want > n_blk) want = n_blk;
   if (want > kMergeMaxSplits) want = kMergeMaxSplits;      // the merge kernel keeps (max, sum) of every split in LDS

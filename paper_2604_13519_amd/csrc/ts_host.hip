@@ -553,6 +553,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   const bool bf = c.dtype == TS_DTYPE_BF16;
   // ---- validation (nothing is modified before it passes) ---------------------------
   int R = 0, max_M = 0, max_keys = 0;
+  long sum_keys = 0;
   for (int s = 0; s < n_seqs; ++s) {
     ts_kv* kv = kvs[s];
     if (!kv) return ts_fail(TS_ERR_INVALID_ARG, "null cache handle (sequence %d)", s);
@@ -573,6 +574,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     R += n + 1;
     max_M = std::max(max_M, n + 1);
     max_keys = std::max(max_keys, kv->P + n + 1);
+    sum_keys += kv->P + n + 1;
   }
   if (!bf && (size_t)max_keys > attn_f32_max_keys())
     return ts_fail(TS_ERR_KV_CAPACITY, "fp32 path supports at most %zu keys per sequence", attn_f32_max_keys());
@@ -580,7 +582,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   (void)hipSetDevice(m->device);
   ts_status st = ensure_workspace(m, R, n_seqs, sample != nullptr);
   if (st) return st;
-  const int splits = bf ? attn_bf16_splits(m, max_keys, n_seqs) : 1;
+  const int splits = bf ? attn_bf16_splits(m, max_keys, n_seqs, sum_keys) : 1;
   if ((st = ensure_attn_partials(m, splits, R))) return st;
 
   // ---- per-row bookkeeping (Alg. 1: flattened sequence + tree mask) ------------------
