@@ -336,10 +336,14 @@ bool shape_supports(int shape, int mode) {
   return true;
 }
 
+// plan.shape values from here on name a many-row configuration: kRowsShape0 + 4 * row tiles + cfg
+constexpr int kRowsShape0 = 100;
+constexpr size_t kRowsPartCap = (size_t)64 << 20;   // partial-sum elements a plan may use before a workspace exists
+
 }  // namespace
 
 int gemm_bf16_cols_per_group(int shape) { return kShapeNT[shape] * kShapeCS[shape] * 16; }
-int gemm_bf16_chunk(int shape) { return kShapeKC[shape]; }
+int gemm_bf16_chunk(int shape) { return shape >= kRowsShape0 ? gemm_rows_chunk((shape - kRowsShape0) % 4) : kShapeKC[shape]; }
 
 // Tile shape and cross-workgroup K splits, from a byte count per CU:
 //   rounds x (weight bytes one workgroup streams)         rounds = ceil(workgroups / CUs)
@@ -349,6 +353,11 @@ int gemm_bf16_chunk(int shape) { return kShapeKC[shape]; }
 // overlap), which the round count models.  mode: 0 partial sums, 1 arg-max (no split),
 // 2 SwiGLU epilogue (no split).
 GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
+  if (R > TS_MROWS_PER_BLOCK && mode != MODE_ARGMAX) {   // batches: the many-row kernel
+    int mt, cfg, splits;
+    const size_t max_part = m->part_elems ? m->part_elems : kRowsPartCap;
+    if (gemm_rows_plan(m, R, N, K, mode, max_part, &mt, &cfg, &splits)) return GemmPlan{kRowsShape0 + mt * 4 + cfg, splits};
+  }
   GemmPlan best{mode == MODE_SWIGLU ? 1 : 0, 1};
   double best_cost = 1e300;
   const int rows = R > TS_MROWS_PER_BLOCK ? TS_MROWS_PER_BLOCK : ((R + 15) / 16) * 16;
@@ -379,6 +388,11 @@ GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
 
 void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, GemmPlan plan,
                       int mode, float* logits, bf16_t* act_out) {
+  if (plan.shape >= kRowsShape0) {
+    const int code = plan.shape - kRowsShape0;
+    launch_gemm_rows_bf16(m, X, Wt, out, R, N, K, code / 4, code % 4, plan.splits, mode, act_out);
+    return;
+  }
   GemmArgs a;
   a.x_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * K;
   a.X = X; a.Wt = Wt; a.out = out; a.logits = logits;

@@ -124,7 +124,7 @@ static void free_workspace(ts_model* m) {
   m->attn_part_o = m->attn_part_ml = nullptr; m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr;
   m->logits = nullptr; m->meta_dev = nullptr; m->seq_dev = nullptr; m->meta_host = nullptr; m->res_host = nullptr;
   m->samp_lse = nullptr; m->samp_tok = nullptr;
-  m->ws_rows = 0; m->ws_seqs = 0; m->logits_rows = 0; m->attn_max_splits = 0;
+  m->ws_rows = 0; m->ws_seqs = 0; m->logits_rows = 0; m->attn_max_splits = 0; m->part_elems = 0;
 }
 
 static size_t meta_bytes_for(int rows) { return (size_t)rows * (6 * sizeof(int32_t) + sizeof(uint64_t) + sizeof(float)); }
@@ -157,6 +157,8 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs, bool want_log
       for (int i = 0; i < 4; ++i) {
         pe = std::max(pe, (size_t)gemm_bf16_plan(m, cap, Ns[i], Ks[i], 0).splits * cap * Ns[i]);
         pe = std::max(pe, (size_t)16 * std::min(cap, TS_MROWS_PER_BLOCK) * Ns[i]);
+        // batches: room for up to 8 splits of the un-fused projections (the planner stays within part_elems)
+        if (cap > TS_MROWS_PER_BLOCK && i != 2) pe = std::max(pe, std::min((size_t)8 * cap * Ns[i], (size_t)64 << 20));
       }
     } else {
       pe = (size_t)cap * std::max(std::max(m->qkv_dim, 2 * c.d_ffn), c.d_model);

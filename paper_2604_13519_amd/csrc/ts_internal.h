@@ -138,6 +138,11 @@ int gemm_bf16_cols_per_group(int shape);
 int gemm_bf16_chunk(int shape);
 void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K,
                       GemmPlan plan, int mode, float* logits, bf16_t* act_out);
+// many-row projection (ts_gemm_rows_bf16.hip), reached through gemm_bf16_plan / launch_gemm_bf16 when R > 80
+bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max_part_elems, int* mt, int* cfg, int* splits);
+int gemm_rows_chunk(int cfg);
+void launch_gemm_rows_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, int mt, int cfg,
+                           int splits, int mode, bf16_t* act_out);
 int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs, long sum_keys);
 void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int layer, int splits, int max_M);
 void launch_attn_merge(ts_model* m, int R, int splits);

@@ -311,6 +311,45 @@ def test_batched_verify_equals_per_sequence_verify(cfg_name, n_seqs):
             B.ts_kv_free(kv)
 
 
+@pytest.mark.parametrize("cfg_name,total_rows", [("small_bf16", 81), ("small_bf16", 112), ("small_bf16", 128),
+                                                 ("small_bf16", 129), ("small_bf16_hd64", 209), ("small_bf16", 400)])
+def test_many_row_projection_row_counts(cfg_name, total_rows):
+    """Passes of more than 80 rows take the many-row projection kernel.  Row totals on both sides
+    of its tile and block edges (81 = 6 row tiles with 15 idle rows, 128 = 8 full tiles, 129, ...):
+    every sequence must get what its own single pass (skinny kernel) gets, and the first two are
+    checked against the oracle."""
+    cfg, w, model, omodel = U.get_model(cfg_name)
+    rng = np.random.default_rng(1000 + total_rows)
+    n_seqs = (total_rows + 64) // 65
+    rows = [total_rows // n_seqs + (1 if s < total_rows % n_seqs else 0) for s in range(n_seqs)]
+    assert sum(rows) == total_rows and max(rows) <= 65
+    kvs, trees, singles = [], [], []
+    try:
+        for s in range(n_seqs):
+            P = int(rng.integers(20, 300))
+            K, V = wl.gen_context_kv(cfg, P, seed=500 + s)
+            kv, okv = U.make_pair(cfg, model, K, V, int(rng.integers(cfg.vocab)), capacity=P + 70)
+            tok, par = _random_tree(rng, rows[s] - 1, cfg.vocab)
+            kvs.append(kv)
+            trees.append((tok, par))
+            if s < 2:
+                res, _ = U.check_verify(cfg, model, omodel, kv, okv, tok, par, check_kv=False,
+                                        label="%s rows %d seq %d" % (cfg_name, total_rows, s))
+            else:
+                res = B.ts_verify(model, kv, tok, par)
+            singles.append((res, B.ts_get_logits(model, 0, rows[s], cfg.vocab)))
+        batch = B.ts_verify_batch(model, kvs, trees)
+        row = 0
+        for s in range(n_seqs):
+            lg = B.ts_get_logits(model, row, rows[s], cfg.vocab)
+            assert U.rel_l2(lg, singles[s][1]) <= 2e-3, "sequence %d" % s   # accumulation order only
+            assert batch[s] == singles[s][0], "sequence %d" % s
+            row += rows[s]
+    finally:
+        for kv in kvs:
+            B.ts_kv_free(kv)
+
+
 # ------------------------------------------------------------------------------------
 # boundary: error paths (forced from the host; every kernel still exits normally)
 # ------------------------------------------------------------------------------------
