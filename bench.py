@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the tree-verify step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload w3|w2|dev]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload w3|w2|w4|dev]
 
 A step is one pass of the whole hot path over one draft tree: ts_verify (tree ingest,
 32-layer masked forward pass, fused vocab arg-max, acceptance walk, result to host) followed
@@ -20,6 +20,12 @@ its mean duration between HIP events on the library's stream, measured in a seco
 event-bracketed repeat of the same steps right after the timed region (bracketing every
 launch inside the timed region itself would slow the step).  `cpu_baseline` is the CPU
 oracle, as it stands, on a bounded sample of the same workload.
+
+--workload w4 times the batched pass instead (16 paged requests, contexts U[2048, 16384], a
+32-node tree each: 528 rows through ts_verify_batch, then one commit per request).  Its
+projections are bound by the matrix cores, so its `roofline` is for the gate/up launch against
+the dense bf16 MFMA peak, counting both bf16 planes of the activations (2 x 2 x R x N x K flop);
+`step_hbm_frac` is the whole step against HBM as for the other workloads.
 """
 import argparse
 import json
@@ -40,7 +46,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="w3", choices=["w3", "w2", "dev"])
+    ap.add_argument("--workload", default="w3", choices=["w3", "w2", "w4", "dev"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -100,6 +106,76 @@ def cpu_baseline(wl, cfg, weights, K, V, root, tree, mean_tokens):
             "est_step_s": full}
 
 
+def main_batched(a, wl, B, torch):
+    """w4: one step = ts_verify_batch over 16 requests + 16 commits + host roll-back."""
+    cfg = wl.get_config("llama8b")
+    weights = wl.gen_weights(cfg, 1234)
+    model = B.ts_model_load(cfg, weights)
+    contexts = [int(x) for x in np.random.default_rng([2345, 4]).integers(2048, 16385, size=16)]
+    kvs, trees, roots = [], [], []
+    for b, P in enumerate(contexts):
+        K, V = wl.gen_context_kv(cfg, P, seed=2345 + b)
+        kv = B.ts_kv_alloc(model, P + 80)
+        B.ts_kv_import(kv, K, V)
+        roots.append(wl.root_token(cfg.vocab, P, seed=3456 + b))
+        B.ts_set_pending(kv, roots[-1])
+        kvs.append(kv)
+        trees.append(wl.bfs_tree([], 32, cfg.vocab, np.random.default_rng([3456, 4, b])))
+        print("[bench] request %d: context %d resident" % (b, P), file=sys.stderr, flush=True)
+    R = sum(len(t[0]) + 1 for t in trees)
+
+    def step():
+        res = B.ts_verify_batch(model, kvs, trees)
+        for kv, P, root in zip(kvs, contexts, roots):
+            B.ts_kv_commit(kv)
+            B.ts_kv_truncate(kv, P)
+            B.ts_set_pending(kv, root)
+        return sum(r[0] + 1 for r in res)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    emitted = 0
+    for _ in range(a.steps):
+        emitted += step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        B.ts_verify_batch(model, kvs, trees)
+    verify_ms = (time.perf_counter() - t0) / a.steps * 1e3
+    B.ts_profile_enable(model, True)
+    B.ts_verify_batch(model, kvs, trees)
+    kernels = {k: {"launches_per_step": n, "avg_us": ms / n * 1e3, "ms_per_step": ms}
+               for k, (n, ms) in B.ts_profile_read(model).items()}
+    B.ts_profile_enable(model, False)
+    dom = "gemm_gate_up"
+    flop = 2.0 * 2.0 * R * (2 * cfg.d_ffn) * cfg.d_model
+    achieved = flop / (kernels[dom]["avg_us"] * 1e-6) / 1e12
+    total_bytes = 2 * cfg.streamed_params() + sum(contexts) * cfg.kv_bytes_per_token()
+    out = {
+        "metric": "accepted tokens/s of single-pass tree verification (verify + commit), 8B bf16; "
+                  "with verify-step latency and % of HBM roofline",
+        "value": emitted / dt, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama3-8b-shape bf16, batch 16, paged contexts U[2048,16384], 32-node BFS trees",
+                   "batch": 16, "rows": R, "context_total": int(sum(contexts))},
+        "verify_ms": verify_ms, "mean_tokens_per_step": emitted / a.steps,
+        "step_algorithmic_gb": total_bytes / 1e9,
+        "step_hbm_frac": total_bytes / (verify_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": achieved / 2500.0, "traffic": None, "flop_per_launch": flop,
+                     "avg_us": kernels[dom]["avg_us"]},
+        "kernels": kernels,
+    }
+    for kv in kvs:
+        B.ts_kv_free(kv)
+    B.ts_model_free(model)
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -115,6 +191,8 @@ def main():
     from paper_2604_13519_amd import binding as B
     B.load_library()
 
+    if a.workload == "w4":
+        return main_batched(a, wl, B, torch)
     cfg_name, P, tree_kind, desc = workload(a.workload)
     cfg = wl.get_config(cfg_name)
     t0 = time.time()
