@@ -47,7 +47,7 @@ struct AttnArgs {
   const bf16_t* Qb;          // [rows][Hq*HD], IEEE half bit patterns
   const uint64_t* row_anc;   // [rows]
   const SeqDesc* seqs;
-  float* part_o;             // [splits][R][Hq][HD]
+  uint16_t* part_o;          // [splits][R][Hq][HD], IEEE half: the split's output divided by its row sum
   float* part_ml;            // [splits][R][Hq][2]
   int layer, Hq, Hkv, R, splits, n_seqs;
   float scale;               // 1/sqrt(head_dim) * log2(e): scores are kept in log2 units
@@ -303,6 +303,10 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
   }
 
   // ---- partial results of this split ---------------------------------------------------
+  // (reference, row sum) in fp32 and the split's own normalised output O / l in half: a convex
+  // combination of V rows, so it can neither overflow nor lose more than half's 11 bits, the
+  // precision the probabilities already have.  Half the bytes of fp32 partials, which is what
+  // bounds this epilogue and the merge kernel.
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const float l = l_run[mt];     // already the sum over all keys (MFMA reduces over the lane groups)
@@ -313,9 +317,11 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
         a.part_ml[base * 2 + 0] = m_run[mt];
         a.part_ml[base * 2 + 1] = l;
       }
+      const float inv = l > 0.f ? 1.0f / l : 0.f;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
-        *reinterpret_cast<f32x4*>(a.part_o + base * HD + dt * 16 + g4 * 4) = o[dt][mt];
+        *reinterpret_cast<u32x2*>(a.part_o + base * HD + dt * 16 + g4 * 4) =
+            u32x2{pack_f16x2(o[dt][mt][0] * inv, o[dt][mt][1] * inv), pack_f16x2(o[dt][mt][2] * inv, o[dt][mt][3] * inv)};
     }
   }
   };
@@ -323,36 +329,36 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
   else body(std::integral_constant<int, (MT1 > 0 ? MT1 : MT0)>{});
 }
 
-// Combine the splits: out = sum_s 2^(m_s - m*) O_s / sum_s 2^(m_s - m*) l_s, stored as (hi, lo) bf16.
+// Combine the splits: out = sum_s w_s (O_s / l_s) / sum_s w_s with w_s = 2^(m_s - m*) l_s, stored as (hi, lo) bf16.
 // One workgroup per (row, head): its 256 threads form 256/(HD/4) groups, group j takes splits
 // j, j+groups, ... so that every partial of the slot is requested at once (the kernel is a
 // single round of memory latency plus the transfer); the groups' sums are then added through
 // LDS in a fixed order.
 constexpr int kMergeMaxSplits = 512;
 
-__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+__global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__ part_o, const float* __restrict__ part_ml,
                                                     bf16_t* __restrict__ Ab, size_t lo_plane, int R, int Hq, int HD, int splits) {
   __shared__ float s_m[kMergeMaxSplits], s_l[kMergeMaxSplits];
   __shared__ float4 r_num[256];
   __shared__ float r_den[256];
   const int tid = threadIdx.x;
-  const int tpp = HD / 4;                  // threads per group: one float4 of the head each
+  const int tpp = HD / 4;                  // threads per group: four dims of the head each
   const int groups = 256 / tpp;
   const int grp = tid / tpp, d4 = tid % tpp;
   const size_t n_slots = (size_t)R * Hq;
   const size_t slot = blockIdx.x;
   const float2* ml = reinterpret_cast<const float2*>(part_ml);
-  const float4* po = reinterpret_cast<const float4*>(part_o);
+  const uint2* po = reinterpret_cast<const uint2*>(part_o);     // 4 halves
   for (int sp = tid; sp < splits; sp += 256) {
     const float2 v = ml[(size_t)sp * n_slots + slot];
     s_m[sp] = v.x;
     s_l[sp] = v.y;
   }
-  float4 o4[4];
+  uint2 o4[4];
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const int sp = grp + u * groups;
-    o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_float4(0.f, 0.f, 0.f, 0.f);
+    o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_uint2(0u, 0u);
   }
   __syncthreads();
   float mstar = -INFINITY;
@@ -364,16 +370,17 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ pa
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int sp = s0 + grp + u * groups;
-        o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_float4(0.f, 0.f, 0.f, 0.f);
+        o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_uint2(0u, 0u);
       }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int sp = s0 + grp + u * groups;
       if (sp < splits && s_m[sp] != -INFINITY) {
-        const float w = exp2f(s_m[sp] - mstar);          // whole-number references: an exact power of two
-        den += w * s_l[sp];
-        num.x += w * o4[u].x; num.y += w * o4[u].y; num.z += w * o4[u].z; num.w += w * o4[u].w;
+        const float w = exp2f(s_m[sp] - mstar) * s_l[sp];   // whole-number references: an exact power of two
+        den += w;
+        const ts_f16x2 lo2 = __builtin_bit_cast(ts_f16x2, o4[u].x), hi2 = __builtin_bit_cast(ts_f16x2, o4[u].y);
+        num.x += w * (float)lo2[0]; num.y += w * (float)lo2[1]; num.z += w * (float)hi2[0]; num.w += w * (float)hi2[1];
       }
     }
   }

@@ -121,7 +121,7 @@ static void free_workspace(ts_model* m) {
   if (m->meta_host) (void)hipHostFree(m->meta_host);
   if (m->res_host) (void)hipHostFree(m->res_host);
   m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr;
-  m->attn_part_o = m->attn_part_ml = nullptr; m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr;
+  m->attn_part_o = nullptr; m->attn_part_ml = nullptr; m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr;
   m->logits = nullptr; m->meta_dev = nullptr; m->seq_dev = nullptr; m->meta_host = nullptr; m->res_host = nullptr;
   m->samp_lse = nullptr; m->samp_tok = nullptr;
   m->ws_rows = 0; m->ws_seqs = 0; m->logits_rows = 0; m->attn_max_splits = 0; m->part_elems = 0;
@@ -196,10 +196,10 @@ static ts_status ensure_attn_partials(ts_model* m, int splits, int R) {
   if (need <= (size_t)m->attn_max_splits) return TS_OK;   // attn_max_splits counts split*row slots
   TS_HIP(hipStreamSynchronize(m->stream));
   dev_free(m->attn_part_o); dev_free(m->attn_part_ml);
-  m->attn_part_o = m->attn_part_ml = nullptr;
+  m->attn_part_o = nullptr; m->attn_part_ml = nullptr;
   m->attn_max_splits = 0;
   ts_status st;
-  if ((st = dev_alloc_bytes((void**)&m->attn_part_o, need * m->q_dim * 4, true))) return st;
+  if ((st = dev_alloc_bytes((void**)&m->attn_part_o, need * m->q_dim * 2, true))) return st;
   if ((st = dev_alloc_bytes((void**)&m->attn_part_ml, need * m->cfg.n_q_heads * 2 * 4, true))) return st;
   m->attn_max_splits = (int)need;
   return TS_OK;
@@ -335,7 +335,7 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   m->stream = nullptr;
   m->embed = m->lm_head = nullptr; m->norm_f = nullptr;
   m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr; m->part_elems = 0;
-  m->attn_part_o = m->attn_part_ml = nullptr; m->attn_max_splits = 0;
+  m->attn_part_o = nullptr; m->attn_part_ml = nullptr; m->attn_max_splits = 0;
   m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr; m->logits = nullptr;
   m->keep_logits = false; m->logits_rows = 0; m->meta_dev = nullptr; m->meta_host = nullptr; m->meta_bytes = 0;
   m->seq_dev = nullptr; m->res_host = nullptr; m->ws_rows = 0; m->ws_seqs = 0;

@@ -92,7 +92,7 @@ struct ts_model {
   void* Fb;                     // SwiGLU product [rows][F]; bf16 models: hi/lo planes
   float* part;                  // split-K partial sums, [S][rows][N] fp32
   size_t part_elems;
-  float* attn_part_o;           // [splits][rows][Hq][hd]
+  uint16_t* attn_part_o;        // [splits][rows][Hq][hd], IEEE half (each split's normalised output)
   float* attn_part_ml;          // [splits][rows][Hq][2]
   int attn_max_splits;
   float2* rope_cs;              // [rows][hd/2] (cos, sin)
