@@ -70,12 +70,14 @@ enum { TS_MAX_NODES = 64, TS_PAGE_SIZE = 16 };
 /* Decoder shape: pre-norm blocks with RMSNorm, rotary embedding (pair (j, j+hd/2)
  * rotated by pos * rope_theta^(-2j/hd)), grouped-query attention with softmax scale
  * 1/sqrt(head_dim), SwiGLU feed-forward, no biases, untied embedding / lm_head.
- * dtype is the storage type of weights and KV cache.  TS_DTYPE_BF16 computes the
- * projections with bf16 MFMA and fp32 accumulation (activations enter as hi+lo
- * pairs of bf16 values), the attention products in IEEE half with fp32 soft-max,
- * keeps the residual stream and logits in fp32, and needs d_model,
- * n_q_heads*head_dim and d_ffn to be multiples of 128 and head_dim 64 or 128.
- * TS_DTYPE_F32 computes in fp32. */
+ * dtype is the storage type of weights and KV cache.  TS_DTYPE_BF16 computes every
+ * matrix product in IEEE half with fp32 accumulation (MFMA): the bf16 weights are
+ * re-encoded as half once at load - exact, half has more significand bits; a finite
+ * weight beyond half's range (|w| > 65504) makes ts_model_load fail with INVALID_ARG -
+ * activations are rounded to half (saturating) where they enter a projection, bf16
+ * K/V entries widen to half exactly, soft-max is fp32, and the residual stream and the
+ * logits stay fp32.  It needs d_model, n_q_heads*head_dim and d_ffn to be multiples of
+ * 128 and head_dim 64 or 128.  TS_DTYPE_F32 computes in fp32. */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rope_theta, rms_eps;
@@ -119,7 +121,7 @@ ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, float* host_l
 /* Final normalised hidden state (the input of the lm_head) of one row of the most recent
  * verify, d_model floats: for row 0 after ingesting a question this is the last-token
  * representation h_x that retrieval compares with the datastore (Sec. 4.3, Eq. 3).  bf16
- * models hold it as a (hi, lo) pair of bf16 values; their exact sum is returned.  STATE if
+ * models hold it in IEEE half (the lm_head's input); it is widened exactly.  STATE if
  * the row is outside the last verify. */
 ts_status ts_get_hidden(ts_model* m, int32_t row, float* host_hidden);
 

@@ -24,19 +24,21 @@ RoPE with inv_freq_j = theta^(-2j/hd), GQA, SwiGLU, no biases, untied head).
 
 Arithmetic: float64 throughout.  Two modes for models stored in bfloat16:
   mode "E"  exact float64 math on the stored (bf16-valued) weights and context.
-  mode "R"  same float64 math, but values are rounded to bfloat16 (nearest
-            even, via float32) at the points where the device path stores or
-            feeds 16-bit values.  bf16: new K/V cache entries.  IEEE half (the
-            attention products run in half precision; bf16 K/V entries widen
-            to it exactly in its normal range): the rotated Q and the
+  mode "R"  same float64 math, but values are rounded (nearest even, via float32)
+            at the points where the device path stores or feeds 16-bit values.
+            bfloat16: new K/V cache entries.  IEEE half, the format of the paper's
+            own runs (App. B, "Performance Comparison", Table 5: the one accuracy
+            deviation is put down to fp16 precision): every activation that enters a weight projection - the
+            normalised activations, the attention output and the SwiGLU product,
+            saturating at the largest finite half - the rotated Q, and the
             unnormalised softmax probabilities entering the P.V product (taken
-            relative to the row maximum rounded up to a whole power of two,
-            see forward_tree).  Pairs of bf16 values
-            (hi + lo, about 16 significant bits): every activation that enters
-            a weight projection - the normalised activations, the attention
-            output and the SwiGLU product.  The residual stream and the logits
-            are never rounded.  Integer decisions (argmax, acceptance) are compared in
-            this mode so both sides decide in the same precision.
+            relative to the row maximum rounded up to a whole power of two, see
+            forward_tree).  bf16 K/V entries and bf16 weights widen to half
+            exactly in half's normal range; the device re-encodes the projection
+            weights as half once at load (magnitudes below 2^-14 move by less than
+            3e-8; not modelled here).  The residual stream and the logits are never
+            rounded.  Integer decisions (argmax, acceptance) are compared in this
+            mode so both sides decide in the same precision.
 
 Pins (tests/test_oracle_*.py): brute-force agreement with an independently
 written dense causal decoder on every root-to-node path; chain == causal
@@ -67,16 +69,14 @@ def bf16_round(x):
     return r.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
 
 
-def bf16_split_round(x):
-    """Value carried as a pair of bfloat16 numbers, hi = bf16(x) and lo = bf16(x - hi):
-    returns hi + lo (about 16 significant bits)."""
-    hi = bf16_round(x)
-    return hi + bf16_round(np.asarray(x, dtype=np.float64) - hi)
-
-
 def fp16_round(x):
     """Round float64 -> float32 -> IEEE half (nearest even), returned as float64."""
     return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float16).astype(np.float64)
+
+
+def fp16_act_round(x):
+    """Activation entering a projection: IEEE half, saturating at the largest finite half."""
+    return fp16_round(np.clip(np.asarray(x, dtype=np.float64), -65504.0, 65504.0))
 
 
 def _widen(a):
@@ -205,7 +205,7 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None, return_
     cfg = model.cfg
     rounding = mode == "R" and cfg.dtype == DTYPE_BF16
     rb = bf16_round if rounding else (lambda a: a)               # single bf16 value
-    rb2 = bf16_split_round if rounding else (lambda a: a)        # hi + lo bf16 pair (projection inputs)
+    ra = fp16_act_round if rounding else (lambda a: a)           # projection inputs: half, saturating
     rh = fp16_round if rounding else (lambda a: a)               # half precision (attention operands)
     M = len(tok)
     P = kv.P
@@ -219,7 +219,7 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None, return_
     newK = np.zeros((cfg.n_layers, M, Hkv, hd))
     newV = np.zeros((cfg.n_layers, M, Hkv, hd))
     for l in range(L):
-        Xn = rb2(rmsnorm(X, model.tensor("norm1", l), cfg.rms_eps))
+        Xn = ra(rmsnorm(X, model.tensor("norm1", l), cfg.rms_eps))
         Q = (Xn @ model.tensor("wq", l).T).reshape(M, Hq, hd)
         K = (Xn @ model.tensor("wk", l).T).reshape(M, Hkv, hd)
         V = (Xn @ model.tensor("wv", l).T).reshape(M, Hkv, hd)
@@ -250,16 +250,16 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None, return_
             denom = np.sum(p, axis=1, keepdims=True)
             vals = np.concatenate([Vc, V[:, g, :]], axis=0)         # [P+M][hd]
             A[:, h, :] = (p @ vals) / denom
-        A = rb2(A.reshape(M, Hq * hd))
+        A = ra(A.reshape(M, Hq * hd))
         X = X + A @ model.tensor("wo", l).T
 
-        Xn = rb2(rmsnorm(X, model.tensor("norm2", l), cfg.rms_eps))
+        Xn = ra(rmsnorm(X, model.tensor("norm2", l), cfg.rms_eps))
         gate = Xn @ model.tensor("wg", l).T
         up = Xn @ model.tensor("wu", l).T
-        act = rb2(silu(gate) * up)
+        act = ra(silu(gate) * up)
         X = X + act @ model.tensor("wd", l).T
 
-    Xf = rb2(rmsnorm(X, model.tensor("norm_f"), cfg.rms_eps))
+    Xf = ra(rmsnorm(X, model.tensor("norm_f"), cfg.rms_eps))
     logits = Xf @ model.tensor("lm_head").T
     if return_hidden:
         return logits, newK, newV, Xf

@@ -329,7 +329,7 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
   else body(std::integral_constant<int, (MT1 > 0 ? MT1 : MT0)>{});
 }
 
-// Combine the splits: out = sum_s w_s (O_s / l_s) / sum_s w_s with w_s = 2^(m_s - m*) l_s, stored as (hi, lo) bf16.
+// Combine the splits: out = sum_s w_s (O_s / l_s) / sum_s w_s with w_s = 2^(m_s - m*) l_s, stored as IEEE half.
 // One workgroup per (row, head): its 256 threads form 256/(HD/4) groups, group j takes splits
 // j, j+groups, ... so that every partial of the slot is requested at once (the kernel is a
 // single round of memory latency plus the transfer); the groups' sums are then added through
@@ -337,7 +337,7 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
 constexpr int kMergeMaxSplits = 512;
 
 __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                    bf16_t* __restrict__ Ab, size_t lo_plane, int R, int Hq, int HD, int splits) {
+                                                    f16_t* __restrict__ Ab, int R, int Hq, int HD, int splits) {
   __shared__ float s_m[kMergeMaxSplits], s_l[kMergeMaxSplits];
   __shared__ float4 r_num[256];
   __shared__ float r_den[256];
@@ -393,16 +393,8 @@ __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__
     num.x += t.x; num.y += t.y; num.z += t.z; num.w += t.w;
     den += r_den[k * tpp + d4];
   }
-  // the attention output feeds the O projection: (hi, lo) bf16 planes
-  const float o[4] = {num.x / den, num.y / den, num.z / den, num.w / den};
-  bf16_t hi[4], lo[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) split_bf16(o[i], hi[i], lo[i]);
-  uint2 oh, ol;
-  oh.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); oh.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
-  ol.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); ol.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
-  *reinterpret_cast<uint2*>(Ab + slot * HD + d4 * 4) = oh;
-  *reinterpret_cast<uint2*>(Ab + lo_plane + slot * HD + d4 * 4) = ol;
+  // the attention output feeds the O projection as half
+  *reinterpret_cast<uint2*>(Ab + slot * HD + d4 * 4) = make_uint2(pack_f16x2_sat(num.x / den, num.y / den), pack_f16x2_sat(num.z / den, num.w / den));
 }
 
 // Rows are covered by RS waves per head, MT tiles of 16 rows each: (tiles -> RS x MT)
@@ -477,5 +469,5 @@ void launch_attn_merge(ts_model* m, int R, int splits) {
   ProfScope ps(m, "attn_merge");
   const ts_model_config& c = m->cfg;
   hipLaunchKernelGGL(k_attn_merge, dim3(R * c.n_q_heads), dim3(256), 0, m->stream, m->attn_part_o, m->attn_part_ml,
-                     (bf16_t*)m->Ab, act_plane(m, m->q_dim), R, c.n_q_heads, c.head_dim, splits);
+                     (f16_t*)m->Ab, R, c.n_q_heads, c.head_dim, splits);
 }

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 typedef uint16_t bf16_t;
+typedef uint16_t f16_t;    // IEEE half bit pattern in memory
 
 // Pointers that reach a kernel through a descriptor in memory are generic to the compiler and
 // would be accessed with FLAT instructions, whose completion is tied to the LDS counter; casting
@@ -28,12 +29,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, ts_bf16x2));
 }
 
-// value -> (hi, lo) bf16 pair with hi = bf16(x), lo = bf16(x - hi): about 16 significant bits
-__device__ __forceinline__ void split_bf16(float x, bf16_t& hi, bf16_t& lo) {
-  hi = f32_to_bf16(x);
-  lo = f32_to_bf16(x - bf16_to_f32(hi));
-}
-
 // two floats -> packed IEEE half pair (low half = a), round to nearest even
 typedef _Float16 ts_f16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_f16x2(float a, float b) {
@@ -47,6 +42,10 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
   return __builtin_bit_cast(uint16_t, (_Float16)f);
 }
+// activation -> IEEE half, round to nearest even, saturating at the largest finite half (NaN stays NaN)
+__device__ __forceinline__ float sat_f16_range(float f) { return f == f ? fminf(fmaxf(f, -65504.f), 65504.f) : f; }
+__device__ __forceinline__ uint16_t f32_to_f16_sat(float f) { return f32_to_f16_bits(sat_f16_range(f)); }
+__device__ __forceinline__ uint32_t pack_f16x2_sat(float a, float b) { return pack_f16x2(sat_f16_range(a), sat_f16_range(b)); }
 
 __device__ __forceinline__ float ld_f32(const float* p) { return *p; }
 __device__ __forceinline__ float ld_f32(const bf16_t* p) { return bf16_to_f32(*p); }

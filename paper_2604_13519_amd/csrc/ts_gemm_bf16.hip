@@ -1,18 +1,19 @@
-// Skinny-M bf16 projection for gfx950:  out[r][n] = sum_k X[r][k] * W[n][k],  r < R <= 80 per pass.
+// Skinny-M projection of a bf16 model for gfx950:  out[r][n] = sum_k X[r][k] * W[n][k],  r < R <= 80 per pass.
 //
 // With at most a few dozen rows the projection is a weight stream: every weight byte is
 // used once, so the kernel is organised around the HBM read of W and nothing else.
+//  * Arithmetic: IEEE half x IEEE half -> fp32 (v_mfma_f32_16x16x32_f16).  The bf16 weights are
+//    re-encoded as half at model load (exact: half has more significand bits; the load rejects
+//    magnitudes beyond half's range) and the activations arrive rounded to half - 11
+//    significant bits where bf16 has 8, with one MFMA per weight fragment.
 //  * W is pre-tiled at model load into MFMA operand order (see k_repack_tiles): a wave's
-//    16-byte-per-lane global load is one contiguous 1 KiB tile that feeds
-//    v_mfma_f32_16x16x32_bf16 directly as the B operand - no LDS, no shuffles for weights.
+//    16-byte-per-lane global load is one contiguous 1 KiB tile that feeds the MFMA directly as
+//    the B operand - no LDS, no shuffles for weights.
 //  * Each wave owns NT tiles of 16 output features and walks its K range in chunks of KC;
 //    the weights of the next PF chunks are in flight (register ring) while the current one
 //    is multiplied.
 //  * The activations X (R x K, tiny) are shared by the WAVES waves of a workgroup through a
-//    double-buffered LDS chunk and read as A operands with 16-byte LDS loads.  Each activation
-//    is a (hi, lo) pair of bf16 values (about 16 significant bits): two MFMAs per weight
-//    fragment.  The matrix cores idle most of the time in a weight-streaming kernel, so the
-//    extra precision costs no bandwidth.
+//    double-buffered LDS chunk and read as A operands with 16-byte LDS loads.
 //  * K is split two ways.  Inside a workgroup, KW waves share the same output columns and take
 //    alternate k-steps of every chunk; their accumulators are added through LDS in a fixed
 //    order at the end.  Across workgroups (grid.y), partial sums go to a fp32
@@ -22,29 +23,27 @@
 //    little of the second as still fills the chip.
 //  * gate/up variant (SWIGLU): the weight tiles of gate and up alternate, so a wave that owns
 //    two neighbouring tiles holds gate and up of the same 16 features; with no cross-workgroup
-//    split the epilogue applies SiLU(gate) * up and stores the (hi, lo) planes directly.
+//    split the epilogue applies SiLU(gate) * up and stores the product as half directly.
 //  * lm_head variant (ARGMAX): no split; the epilogue reduces each row's maximum over the
 //    workgroup's columns and emits one (value, index) partial per row, so the full logits
 //    never have to reach memory.
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 struct GemmArgs {
-  const bf16_t* X;     // [2][rows][K]: hi plane, then lo plane (x = hi + lo), rows padded in memory
-  size_t x_plane;      // elements between the planes
-  const bf16_t* Wt;    // tiled weights
+  const f16_t* X;      // [rows][K] IEEE half, rows padded in memory
+  const f16_t* Wt;     // tiled weights, IEEE half
   float* out;          // [split][R][N] partial sums (nullptr for ARGMAX)
   float* logits;       // [R][N] or nullptr (ARGMAX only)
   float* aval;         // [R][amax_parts]
   int32_t* aidx;
-  bf16_t* act_out;     // SWIGLU: [2][rows][N/2] hi/lo planes of the gated product
-  size_t act_plane;
+  f16_t* act_out;      // SWIGLU: [rows][N/2] gated product, IEEE half
   int R, N, K;
   int kper;            // k elements per split
   int n_tiles;         // ceil(N / 16)
@@ -67,14 +66,13 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
   constexpr int XS = KC + XPAD;             // LDS row stride in elements (+16 B: bank spread, keeps alignment)
   constexpr int NTHR = 64 * WAVES;
   constexpr int NBUF = PF + 1;              // weight register ring
-  constexpr int XV1 = MT * 16 * KC / 8;     // 16-byte vectors per X chunk and plane
-  constexpr int XV = 2 * XV1;               // both planes
+  constexpr int XV = MT * 16 * KC / 8;      // 16-byte vectors per X chunk
   constexpr int XPT = (XV + NTHR - 1) / NTHR;
-  // activation chunks [buffer][plane][row][k]; the same memory later serves the k-wave reduction
-  constexpr size_t XS_BYTES = sizeof(bf16_t) * 2 * 2 * MT * 16 * XS;
-  constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * MT * 4 * NT * 64 : 0;
+  // activation chunks [buffer][row][k]; the same memory later serves the k-wave reduction
+  constexpr size_t XS_BYTES = sizeof(f16_t) * 2 * MT * 16 * XS;
+  constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * 4 * NT * 64 : 0;
   __shared__ __attribute__((aligned(16))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
-  bf16_t (*xs)[2][MT * 16][XS] = reinterpret_cast<bf16_t (*)[2][MT * 16][XS]>(smem);
+  f16_t (*xs)[MT * 16][XS] = reinterpret_cast<f16_t (*)[MT * 16][XS]>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, g = lane >> 4;
@@ -99,10 +97,9 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
   uint32_t x_off[XPT];                      // byte offset of each staged vector within a chunk
 #pragma unroll
   for (int p = 0; p < XPT; ++p) {
-    const int v = min(tid + p * NTHR, XV - 1);
-    const int pl = v / XV1, u = v % XV1;
-    const int row = u / (KC / 8), cv = u % (KC / 8);
-    x_off[p] = (uint32_t)((pl * a.x_plane + (size_t)row * a.K + cv * 8) * 2);
+    const int v = min(tid + p * NTHR, XV - 1);      // surplus threads re-read the last vector
+    const int row = v / (KC / 8), cv = v % (KC / 8);
+    x_off[p] = (uint32_t)(((size_t)row * a.K + cv * 8) * 2);
   }
 
   f32x4 acc[MT][NT];
@@ -111,52 +108,41 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 w[NBUF][NT][KSW];
+  f16x8 w[NBUF][NT][KSW];
   u32x4 xr[XPT];
 
-  auto load_w = [&](bf16x8 (&dst)[NT][KSW], int chunk) {
+  auto load_w = [&](f16x8 (&dst)[NT][KSW], int chunk) {
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int j = 0; j < KSW; ++j)
         dst[t][j] = __builtin_nontemporal_load(
-            reinterpret_cast<const bf16x8*>(wbase[t] + (size_t)chunk * (KSTEPS * 1024) + w_lane + j * 1024));
+            reinterpret_cast<const f16x8*>(wbase[t] + (size_t)chunk * (KSTEPS * 1024) + w_lane + j * 1024));
   };
   auto load_x = [&](int chunk) {
     const char* xb = xbase + (size_t)chunk * (KC * 2);
 #pragma unroll
-    for (int p = 0; p < XPT; ++p)
-      if (XV % NTHR == 0 || tid + p * NTHR < XV) xr[p] = *reinterpret_cast<const u32x4*>(xb + x_off[p]);
+    for (int p = 0; p < XPT; ++p) xr[p] = *reinterpret_cast<const u32x4*>(xb + x_off[p]);   // never predicated, see below
   };
   auto store_x = [&](int buf) {
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
-      if (XV % NTHR == 0 || v < XV) {
-        const int pl = v / XV1, u = v % XV1;
-        const int row = u / (KC / 8), cv = u % (KC / 8);
-        *reinterpret_cast<u32x4*>(&xs[buf][pl][row][cv * 8]) = xr[p];
-      }
+      if (XV % NTHR == 0 || v < XV) *reinterpret_cast<u32x4*>(&xs[buf][v / (KC / 8)][(v % (KC / 8)) * 8]) = xr[p];
     }
   };
-  // activations are (hi, lo) bf16 pairs: both planes multiply the same weight fragment and
-  // add into the same fp32 accumulator
-  auto mma_chunk = [&](const bf16x8 (&wc)[NT][KSW], int buf) {
+  auto mma_chunk = [&](const f16x8 (&wc)[NT][KSW], int buf) {
 #pragma unroll
     for (int ks = 0; ks < KSW; ++ks) {
-      bf16x8 ah[MT], al[MT];
+      f16x8 xa[MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        ah[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][0][mt * 16 + l15][(kq * KSW + ks) * 32 + g * 8]);
-        al[mt] = *reinterpret_cast<const bf16x8*>(&xs[buf][1][mt * 16 + l15][(kq * KSW + ks) * 32 + g * 8]);
-      }
+      for (int mt = 0; mt < MT; ++mt)
+        xa[mt] = *reinterpret_cast<const f16x8*>(&xs[buf][mt * 16 + l15][(kq * KSW + ks) * 32 + g * 8]);
 #pragma unroll
       for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
-          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
-        }
+        for (int mt = 0; mt < MT; ++mt)
+          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
     }
   };
 
@@ -167,7 +153,7 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
   // and the steady-state trips issue both unconditionally - a prefetch under an `if` would
   // turn every wait for X into a wait for all weights as well.  The last chunks, where
   // there is nothing left to prefetch, run in a predicated tail.
-  auto step = [&](bf16x8 (&wcur)[NT][KSW], bf16x8 (&wnext)[NT][KSW], int c, bool steady) {
+  auto step = [&](f16x8 (&wcur)[NT][KSW], f16x8 (&wnext)[NT][KSW], int c, bool steady) {
     const bool more = steady || c + 1 < n_chunks;
     if (more) load_x(c + 1);
     __builtin_amdgcn_sched_barrier(0);      // X loads first, then the weight prefetch
@@ -207,10 +193,7 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
         const int f = (nt_idx[0] >> 1) * 16 + l15;           // tiles 2j / 2j+1 = gate / up of features 16j..
         if (nt_idx[1] < a.n_tiles) {
           const float gv = v[0], uv = v[NT - 1];
-          bf16_t hi, lo;
-          split_bf16(gv / (1.0f + expf(-gv)) * uv, hi, lo);
-          a.act_out[(size_t)row * (a.N / 2) + f] = hi;
-          a.act_out[a.act_plane + (size_t)row * (a.N / 2) + f] = lo;
+          a.act_out[(size_t)row * (a.N / 2) + f] = f32_to_f16_sat(gv / (1.0f + expf(-gv)) * uv);
         }
       } else {
         float* o = a.out + (size_t)blockIdx.y * a.split_stride;
@@ -233,26 +216,27 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
         }
     } else {
       // add the KW accumulators of a column set through LDS (the activation buffers are free
-      // after the loop's last barrier), always in the order kq = 0, 1, ...
-      constexpr int SLOTS = MT * 4 * NT;
+      // after the loop's last barrier), one row tile at a time, always in the order kq = 0, 1, ...
       float* red = reinterpret_cast<float*>(smem);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
-          for (int t = 0; t < NT; ++t) red[((size_t)wave * SLOTS + (mt * 4 + r) * NT + t) * 64 + lane] = acc[mt][t][r];
-      __syncthreads();
-      for (int q = kq; q < MT * 4; q += KW) {               // this wave finishes rows q of its column set
-        float v[NT];
+          for (int t = 0; t < NT; ++t) red[((wave * 4 + r) * NT + t) * 64 + lane] = acc[mt][t][r];
+        __syncthreads();
+        for (int r = kq; r < 4; r += KW) {                 // this wave finishes rows r of the tile
+          float v[NT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          float sum = 0.f;
+          for (int t = 0; t < NT; ++t) {
+            float sum = 0.f;
 #pragma unroll
-          for (int k = 0; k < KW; ++k) sum += red[((size_t)(cs * KW + k) * SLOTS + q * NT + t) * 64 + lane];
-          v[t] = sum;
+            for (int k = 0; k < KW; ++k) sum += red[(((cs * KW + k) * 4 + r) * NT + t) * 64 + lane];
+            v[t] = sum;
+          }
+          emit(mt, r, v);
         }
-        emit(q >> 2, q & 3, v);
+        __syncthreads();
       }
     }
   } else {
@@ -306,8 +290,8 @@ void launch_mt(int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
 }
 
 // The compiled tile shapes.  shape id -> (NT, CS, KW): tiles per wave, column sets and
-// k-waves per workgroup.  All use chunks of 128 k (the LDS holds two buffers of two planes of
-// the activation chunk, 85 KiB for 80 rows).  The k-wave shapes hold fewer weight registers
+// k-waves per workgroup.  All use chunks of 128 k (the LDS holds two buffers of the
+// activation chunk, 43 KiB for 80 rows).  The k-wave shapes hold fewer weight registers
 // per chunk and prefetch two chunks ahead instead of one.  Shape 5 (96 columns, 6 waves) exists
 // because 6144 output features (the 8B QKV projection) fill 256 CUs as 64 groups x 4 splits
 // but only 192 as 48 x 4.
@@ -377,7 +361,7 @@ GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
       const double kper = (double)K / s;
       double cost = rounds * cols * kper * 2.0;
       if (s > 1) cost += 2.0 * s * R * (double)N * 4.0 / m->n_cu;
-      cost += 0.25 * rounds * rows * kper * 4.0;
+      cost += 0.25 * rounds * rows * kper * 2.0;
       if (kShapeCS[shape] * kShapeKW[shape] < 6) cost *= 1.05;   // 4-wave workgroups hide less latency
       if (kShapeNT[shape] < 2) cost *= 1.05;                     // one tile per wave reads twice the LDS per weight byte
       if (cost < best_cost) { best_cost = cost; best.shape = shape; best.splits = s; }
@@ -386,19 +370,17 @@ GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
   return best;
 }
 
-void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, GemmPlan plan,
-                      int mode, float* logits, bf16_t* act_out) {
+void launch_gemm_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, int R, int N, int K, GemmPlan plan,
+                      int mode, float* logits, f16_t* act_out) {
   if (plan.shape >= kRowsShape0) {
     const int code = plan.shape - kRowsShape0;
     launch_gemm_rows_bf16(m, X, Wt, out, R, N, K, code / 4, code % 4, plan.splits, mode, act_out);
     return;
   }
   GemmArgs a;
-  a.x_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * K;
   a.X = X; a.Wt = Wt; a.out = out; a.logits = logits;
   a.aval = m->amax_val; a.aidx = m->amax_idx;
   a.act_out = act_out;
-  a.act_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * (N / 2);
   a.R = R; a.N = N; a.K = K;
   const int splits = mode == MODE_PARTIAL ? plan.splits : 1;
   a.kper = K / splits;

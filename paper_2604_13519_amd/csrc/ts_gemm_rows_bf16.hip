@@ -1,14 +1,14 @@
-// Many-row bf16 projection for gfx950:  out[r][n] = sum_k X[r][k] * W[n][k]  for R > 80 rows
+// Many-row projection of a bf16 model for gfx950:  out[r][n] = sum_k X[r][k] * W[n][k]  for R > 80 rows
 // (batched verification: the rows of all requests of a pass share one weight stream).
 //
 // With hundreds of rows the projection is no longer a weight stream but a matrix-core problem:
-// every weight fragment is multiplied with R / 16 activation fragments, twice (the activations
-// are (hi, lo) bf16 pairs).  The kernel keeps the data path of the skinny kernel - weights
+// every weight fragment is multiplied with R / 16 activation fragments.  The kernel keeps the
+// arithmetic (IEEE half x half -> fp32) and the data path of the skinny kernel - weights
 // pre-tiled in MFMA operand order and loaded straight from global memory into registers,
 // activations shared through a double-buffered LDS chunk - and changes the tile a wave owns:
 //  * 4 tiles of 16 output features per wave (the skinny kernel has 2).  One 1 KiB activation
-//    fragment read from LDS then feeds 4 MFMAs per plane, 64 matrix-pipe cycles against 8
-//    LDS-pipe cycles; with 8 waves the LDS pipe is half as busy as the four matrix pipes.
+//    fragment read from LDS then feeds 4 MFMAs, 64 matrix-pipe cycles against 8 LDS-pipe
+//    cycles; with 8 waves the LDS pipe is half as busy as the four matrix pipes.
 //  * 4 to 8 row tiles (up to 128 rows) per workgroup.  The rows of a pass are cut into equal
 //    row blocks; the row blocks of one weight slab get consecutive places on the same XCD, so that
 //    the slab comes from HBM once and from that XCD's L2 for the other blocks.
@@ -18,25 +18,23 @@
 //    one row tile at a time, in the order kq = 0, 1, ...; K splits write fp32 partial sums
 //    [split][row][col] for the next row-wise kernel (deterministic, no atomics).
 //  * gate/up variant (SWIGLU): gate and up tiles alternate, a wave holds two (gate, up) pairs
-//    and the epilogue stores the (hi, lo) planes of SiLU(gate) * up.
+//    and the epilogue stores SiLU(gate) * up as half.
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 #include <algorithm>
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 struct RowsArgs {
-  const bf16_t* X;     // [2][x_rows][K]: hi plane, then lo plane
-  size_t x_plane;      // elements between the planes
-  int x_rows;          // rows allocated per plane (reads are clamped to them)
-  const bf16_t* Wt;    // tiled weights
+  const f16_t* X;      // [x_rows][K] IEEE half
+  int x_rows;          // rows allocated (reads are clamped to them)
+  const f16_t* Wt;     // tiled weights, IEEE half
   float* out;          // [split][R][N] partial sums
-  bf16_t* act_out;     // SWIGLU: [2][x_rows][N/2]
-  size_t act_plane;
+  f16_t* act_out;      // SWIGLU: [x_rows][N/2] IEEE half
   int R, N, K;
   int kper;            // k elements per split
   int n_tiles;         // ceil(N / 16)
@@ -60,14 +58,12 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
   static_assert(KSW >= 1 && KSW * KW == KSTEPS, "k-steps of a chunk divide among the k-waves");
   constexpr int XS = KC + 8;                // LDS row stride in elements (+16 B: bank spread)
   constexpr int NTHR = 64 * WAVES;
-  constexpr int XV1 = MT * 16 * KC / 8;     // 16-byte vectors per chunk and plane
-  constexpr int XV = 2 * XV1;
+  constexpr int XV = MT * 16 * KC / 8;      // 16-byte vectors per chunk
   constexpr int XPT = (XV + NTHR - 1) / NTHR;
-  constexpr size_t XS_BYTES = sizeof(bf16_t) * 2 * 2 * MT * 16 * XS;
-  constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * 4 * NT * 64 : 0;
-  static_assert(XS_BYTES >= RED_BYTES, "the reduction reuses the activation buffers");
-  __shared__ __attribute__((aligned(16))) char smem[XS_BYTES];
-  bf16_t (*xs)[2][MT * 16][XS] = reinterpret_cast<bf16_t (*)[2][MT * 16][XS]>(smem);
+  constexpr size_t XS_BYTES = sizeof(f16_t) * 2 * MT * 16 * XS;
+  constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * 4 * NT * 64 : 0;   // the reduction reuses the activation buffers
+  __shared__ __attribute__((aligned(16))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
+  f16_t (*xs)[MT * 16][XS] = reinterpret_cast<f16_t (*)[MT * 16][XS]>(smem);
 
   // place: XCD = blockIdx.x % 8; the row blocks of a weight slab follow each other on one XCD
   const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
@@ -98,9 +94,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
 #pragma unroll
   for (int p = 0; p < XPT; ++p) {
     const int v = min(tid + p * NTHR, XV - 1);
-    const int pl = v / XV1, u = v % XV1;
-    const int row = min(row0 + u / (KC / 8), a.x_rows - 1), cv = u % (KC / 8);
-    x_off[p] = (uint32_t)((pl * a.x_plane + (size_t)row * a.K + cv * 8) * 2);
+    const int row = min(row0 + v / (KC / 8), a.x_rows - 1), cv = v % (KC / 8);
+    x_off[p] = (uint32_t)(((size_t)row * a.K + cv * 8) * 2);
   }
 
   f32x4 acc[MT][NT];
@@ -109,15 +104,15 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 w[2][NT][KSW];
+  f16x8 w[2][NT][KSW];
   u32x4 xr[XPT];
 
-  auto load_w = [&](bf16x8 (&dst)[NT][KSW], int chunk) {
+  auto load_w = [&](f16x8 (&dst)[NT][KSW], int chunk) {
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int j = 0; j < KSW; ++j)
-        dst[t][j] = *reinterpret_cast<const bf16x8*>(wbase[t] + (size_t)chunk * (KSTEPS * 1024) + w_lane + j * 1024);
+        dst[t][j] = *reinterpret_cast<const f16x8*>(wbase[t] + (size_t)chunk * (KSTEPS * 1024) + w_lane + j * 1024);
   };
   auto load_x = [&](int chunk) {
     const char* xb = xbase + (size_t)chunk * (KC * 2);
@@ -128,29 +123,22 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
-      if (XV % NTHR == 0 || v < XV) {
-        const int pl = v / XV1, u = v % XV1;
-        *reinterpret_cast<u32x4*>(&xs[buf][pl][u / (KC / 8)][(u % (KC / 8)) * 8]) = xr[p];
-      }
+      if (XV % NTHR == 0 || v < XV) *reinterpret_cast<u32x4*>(&xs[buf][v / (KC / 8)][(v % (KC / 8)) * 8]) = xr[p];
     }
   };
-  auto mma_chunk = [&](const bf16x8 (&wc)[NT][KSW], int buf) {
+  auto mma_chunk = [&](const f16x8 (&wc)[NT][KSW], int buf) {
 #pragma unroll
     for (int ks = 0; ks < KSW; ++ks) {
       const int kk = (kq * KSW + ks) * 32 + g * 8;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const bf16x8 ah = *reinterpret_cast<const bf16x8*>(&xs[buf][0][mt * 16 + l15][kk]);
-        const bf16x8 al = *reinterpret_cast<const bf16x8*>(&xs[buf][1][mt * 16 + l15][kk]);
-        // the hi products of all four tiles first: no MFMA waits for the one before it
+        const f16x8 xa = *reinterpret_cast<const f16x8*>(&xs[buf][mt * 16 + l15][kk]);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, wc[t][ks], acc[mt][t], 0, 0, 0);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, wc[t][ks], acc[mt][t], 0, 0, 0);
+        for (int t = 0; t < NT; ++t) acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, wc[t][ks], acc[mt][t], 0, 0, 0);
       }
     }
   };
-  auto step = [&](bf16x8 (&wcur)[NT][KSW], bf16x8 (&wnext)[NT][KSW], int c, bool steady) {
+  auto step = [&](f16x8 (&wcur)[NT][KSW], f16x8 (&wnext)[NT][KSW], int c, bool steady) {
     const bool more = steady || c + 1 < n_chunks;
     if (more) { load_x(c + 1); load_w(wnext, c + 1); }
     mma_chunk(wcur, c & 1);
@@ -182,10 +170,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
         if (nt_idx[t + 1] < a.n_tiles) {
           const int f = (nt_idx[t] >> 1) * 16 + l15;
           const float gv = v[t], uv = v[t + 1];
-          bf16_t hi, lo;
-          split_bf16(gv / (1.0f + expf(-gv)) * uv, hi, lo);
-          a.act_out[(size_t)row * (a.N / 2) + f] = hi;
-          a.act_out[a.act_plane + (size_t)row * (a.N / 2) + f] = lo;
+          a.act_out[(size_t)row * (a.N / 2) + f] = f32_to_f16_sat(gv / (1.0f + expf(-gv)) * uv);
         }
       }
     } else {
@@ -276,12 +261,11 @@ bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max
   const int tiles = (R + 15) / 16;
   double best = 1e300;
   bool found = false;
-  if ((size_t)(R + 2 * TS_MROWS_PER_BLOCK) * K * 4 >= ((size_t)1 << 32)) return false;   // 32-bit activation offsets
+  if ((size_t)(R + 2 * TS_MROWS_PER_BLOCK) * K * 2 >= ((size_t)1 << 32)) return false;   // 32-bit activation offsets
   for (int mt = kMinMT; mt <= kMaxMT; ++mt) {
     const int n_rblocks = (tiles + mt - 1) / mt;
     if (mt > kMinMT && n_rblocks == (tiles + mt - 2) / (mt - 1)) continue;   // same blocks, more idle rows
     for (int cfg = 0; cfg < kNumCfg; ++cfg) {
-      if (mt == 8 && cfg == 2) continue;          // would spill registers
       const int kc = kCfgKC[cfg];
       if (K % kc) continue;
       const int chunks = K / kc;
@@ -292,15 +276,17 @@ bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max
         if (mode != MODE_PARTIAL && s > 1) break;
         if (s > 1 && (size_t)s * R * N > max_part_elems) break;
         const long wgs = (long)((groups * s + 7) / 8) * 8 * n_rblocks;
-        // the 4-row-tile 8x1 kernel needs half the registers and LDS of a CU: two workgroups share one
-        const int wg_per_cu = (cfg == 0 && mt <= 4) ? 2 : 1;
+        // the 4-row-tile kernels with one or two k-waves need half the registers and LDS of a CU:
+        // two workgroups share one
+        const int wg_per_cu = (cfg <= 1 && mt <= 4) ? 2 : 1;
         const long rounds = (wgs + (long)m->n_cu * wg_per_cu - 1) / ((long)m->n_cu * wg_per_cu);
         // MFMAs a SIMD issues for one workgroup (2 waves per SIMD), 16 cycles each at 2.4 GHz;
-        // measured issue efficiency is about one half, a little less with more k-waves
-        const double eff = cfg == 0 ? 0.50 : cfg == 1 ? 0.47 : 0.42;
-        const double mfma_us = 2.0 * (K / s / 32 / kCfgKW[cfg]) * mt * NT * 2 * 16 / 2400.0;
+        // measured issue efficiency: about 0.36 with four waves per SIMD, 0.30 with two, a tenth
+        // less with four k-waves
+        const double eff = (wg_per_cu == 2 ? 0.36 : 0.30) * (cfg == 2 ? 0.9 : 1.0);
+        const double mfma_us = 2.0 * (K / s / 32 / kCfgKW[cfg]) * mt * NT * 16 / 2400.0;
         double cost = rounds * (wg_per_cu * mfma_us / eff + 6.0);
-        if (s > 1) cost += s * R * (double)N * 4.0 / 6.0e6;         // partial sums written at ~6 TB/s
+        if (s > 1) cost += s * R * (double)N * 4.0 / 12.0e6;        // partial sums, mostly overlapped with the products
         if (cost < best) { best = cost; found = true; *mt_out = mt; *cfg_out = cfg; *splits_out = s; }
       }
     }
@@ -308,14 +294,12 @@ bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max
   return found;
 }
 
-void launch_gemm_rows_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, int mt, int cfg,
-                           int splits, int mode, bf16_t* act_out) {
+void launch_gemm_rows_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, int R, int N, int K, int mt, int cfg,
+                           int splits, int mode, f16_t* act_out) {
   RowsArgs a;
   a.x_rows = m->ws_rows + TS_MROWS_PER_BLOCK;
-  a.x_plane = (size_t)a.x_rows * K;
   a.X = X; a.Wt = Wt; a.out = out;
   a.act_out = act_out;
-  a.act_plane = (size_t)a.x_rows * (N / 2);
   a.R = R; a.N = N; a.K = K;
   if (mode != MODE_PARTIAL) splits = 1;
   a.kper = K / splits;

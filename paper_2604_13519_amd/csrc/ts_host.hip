@@ -58,6 +58,21 @@ static inline float bf16_bits_to_float(uint16_t u) {
   memcpy(&f, &b, 4);
   return f;
 }
+static inline float half_bits_to_float(uint16_t h) {
+  const uint32_t sign = (uint32_t)(h & 0x8000u) << 16, e = (h >> 10) & 0x1fu, f = h & 0x3ffu;
+  uint32_t bits;
+  if (e == 0x1fu) bits = sign | 0x7f800000u | (f << 13);                      // inf / NaN
+  else if (e != 0) bits = sign | ((e + 112u) << 23) | (f << 13);              // normal
+  else if (f == 0) bits = sign;                                               // zero
+  else {                                                                      // subnormal: f * 2^-24
+    float v = (float)f * 5.9604644775390625e-08f;
+    memcpy(&bits, &v, 4);
+    bits |= sign;
+  }
+  float out;
+  memcpy(&out, &bits, 4);
+  return out;
+}
 
 template <typename T>
 static ts_status dev_alloc(T** p, size_t count) {
@@ -143,11 +158,10 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs, bool want_log
     const int scap = std::max(seqs, 1);
     const size_t esz = m->esz;
     if ((st = dev_alloc_bytes((void**)&m->H, (size_t)alloc_rows * c.d_model * 4, true))) return st;
-    const size_t planes = c.dtype == TS_DTYPE_BF16 ? 2 : 1;     // bf16 projection inputs are (hi, lo) pairs
-    if ((st = dev_alloc_bytes(&m->Xn, planes * alloc_rows * c.d_model * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Xn, (size_t)alloc_rows * c.d_model * esz, true))) return st;   // bf16 models: IEEE half
     if ((st = dev_alloc_bytes(&m->Qb, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Ab, planes * alloc_rows * m->q_dim * esz, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Fb, planes * alloc_rows * c.d_ffn * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Ab, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Fb, (size_t)alloc_rows * c.d_ffn * esz, true))) return st;
     size_t pe = 0;
     if (c.dtype == TS_DTYPE_BF16) {
       const int Ns[4] = {m->qkv_dim, c.d_model, 2 * c.d_ffn, c.d_model};
@@ -206,14 +220,15 @@ static ts_status ensure_attn_partials(ts_model* m, int splits, int R) {
 }
 
 // Upload one host matrix [N][K] and leave it on the device in the layout its GEMM reads.
-// bf16: staged row-major, then re-tiled into dst at tile offset n_tile0 (stride n_tile_stride).
+// bf16: staged row-major, then re-tiled as IEEE half into dst at tile offset n_tile0 (stride
+//       n_tile_stride); m->range_flag collects weights that half cannot hold.
 // f32 : copied row-major to dst + row_off rows.
 static ts_status upload_matrix(ts_model* m, const void* host, int N, int K, void* dst, void* staging, int n_tile0,
                                int n_tile_stride, int f32_row_off) {
   if (!host) return ts_fail(TS_ERR_INVALID_ARG, "null weight pointer");
   if (m->cfg.dtype == TS_DTYPE_BF16) {
     TS_HIP(copy_sync(m->stream, staging, host, (size_t)N * K * 2, hipMemcpyHostToDevice));
-    launch_repack_tiles(m->stream, (const bf16_t*)staging, (bf16_t*)dst, N, K, n_tile0, n_tile_stride);
+    launch_repack_tiles(m->stream, (const bf16_t*)staging, (f16_t*)dst, N, K, n_tile0, n_tile_stride, m->range_flag);
     TS_HIP(hipGetLastError());
     TS_HIP(hipStreamSynchronize(m->stream));
   } else {
@@ -253,6 +268,7 @@ static ts_status model_load_impl(ts_model* m, const ts_weights* w) {
     size_t big = std::max((size_t)V * d, (size_t)F * d);
     big = std::max(big, (size_t)m->q_dim * d);
     if ((st = dev_alloc_bytes(&staging, big * 2, false))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->range_flag, sizeof(int), true))) { dev_free(staging); return st; }
   }
   auto matrix_bytes = [&](int N, int K) { return (bf ? tiled_elems(N, K) : (size_t)N * K) * esz; };
 
@@ -302,6 +318,11 @@ static ts_status model_load_impl(ts_model* m, const ts_weights* w) {
     if ((st = upload_gain(m, w->norm2[l], &L.norm2))) break;
   }
   dev_free(staging);
+  if (!st && bf) {       // the projections multiply in IEEE half: every finite weight has to fit its range
+    int flag = 0;
+    TS_HIP(copy_sync(m->stream, &flag, m->range_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (flag) st = ts_fail(TS_ERR_INVALID_ARG, "a projection weight exceeds the IEEE half range (|w| > 65504)");
+  }
   return st;
 }
 
@@ -310,7 +331,7 @@ extern "C" ts_status ts_model_free(ts_model* m) {
   (void)hipSetDevice(m->device);
   if (m->stream) (void)hipStreamSynchronize(m->stream);
   free_workspace(m);
-  dev_free(m->embed); dev_free(m->lm_head); dev_free(m->norm_f);
+  dev_free(m->embed); dev_free(m->lm_head); dev_free(m->norm_f); dev_free(m->range_flag);
   for (LayerW& L : m->layers) {
     dev_free(L.wqkv); dev_free(L.wo); dev_free(L.wgu); dev_free(L.wd); dev_free(L.norm1); dev_free(L.norm2);
   }
@@ -333,7 +354,7 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   m->kv_dim = cfg->n_kv_heads * cfg->head_dim;
   m->qkv_dim = m->q_dim + 2 * m->kv_dim;
   m->stream = nullptr;
-  m->embed = m->lm_head = nullptr; m->norm_f = nullptr;
+  m->embed = m->lm_head = nullptr; m->norm_f = nullptr; m->range_flag = nullptr;
   m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr; m->part_elems = 0;
   m->attn_part_o = nullptr; m->attn_part_ml = nullptr; m->attn_max_splits = 0;
   m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr; m->logits = nullptr;
@@ -630,7 +651,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
       GemmPlan p = gemm_bf16_plan(m, R, N, K, 0);
       while (p.splits > 1 && (size_t)p.splits * R * N > m->part_elems) p.splits = K / gemm_bf16_chunk(p.shape) % (p.splits / 2) == 0 ? p.splits / 2 : 1;
       ProfScope ps(m, name);
-      launch_gemm_bf16(m, (const bf16_t*)X, (const bf16_t*)W, m->part, R, N, K, p, 0, nullptr, nullptr);
+      launch_gemm_bf16(m, (const f16_t*)X, (const f16_t*)W, m->part, R, N, K, p, 0, nullptr, nullptr);
       *n_parts = p.splits;
       *stride = (size_t)R * N;
     } else {
@@ -656,7 +677,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     if (bf) {   // gate/up projection with the SwiGLU product in its epilogue
       const GemmPlan p = gemm_bf16_plan(m, R, 2 * F, d, 2);
       ProfScope psc(m, "gemm_gate_up");
-      launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)L.wgu, nullptr, R, 2 * F, d, p, 2, nullptr, (bf16_t*)m->Fb);
+      launch_gemm_bf16(m, (const f16_t*)m->Xn, (const f16_t*)L.wgu, nullptr, R, 2 * F, d, p, 2, nullptr, (f16_t*)m->Fb);
     } else {
       project("gemm_gate_up", m->Xn, L.wgu, 2 * F, d, &np, &ps);
       launch_swiglu(m, R, np, ps);
@@ -673,7 +694,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   if (bf) {
     const GemmPlan p = gemm_bf16_plan(m, TS_MROWS_PER_BLOCK, c.vocab, d, 1);   // as at load: fixes the partial count
     ProfScope ps(m, "gemm_lm_head_argmax");
-    launch_gemm_bf16(m, (const bf16_t*)m->Xn, (const bf16_t*)m->lm_head, nullptr, R, c.vocab, d, p, 1,
+    launch_gemm_bf16(m, (const f16_t*)m->Xn, (const f16_t*)m->lm_head, nullptr, R, c.vocab, d, p, 1,
                      (m->keep_logits || sample) ? m->logits : nullptr, nullptr);
   } else {
     launch_gemm_f32(m, (const float*)m->Xn, (const float*)m->lm_head, m->logits, R, c.vocab, d);
@@ -762,18 +783,10 @@ extern "C" ts_status ts_get_hidden(ts_model* m, int32_t row, float* host_hidden)
     TS_HIP(copy_sync(m->stream, host_hidden, (const float*)m->Xn + (size_t)row * d, (size_t)d * 4, hipMemcpyDeviceToHost));
     return TS_OK;
   }
-  // bf16 models keep the normalised activations as (hi, lo) bf16 planes: x = hi + lo, exactly representable in fp32
-  std::vector<uint16_t> hi(d), lo(d);
-  const bf16_t* base = (const bf16_t*)m->Xn;
-  TS_HIP(copy_sync(m->stream, hi.data(), base + (size_t)row * d, (size_t)d * 2, hipMemcpyDeviceToHost));
-  TS_HIP(copy_sync(m->stream, lo.data(), base + act_plane(m, d) + (size_t)row * d, (size_t)d * 2, hipMemcpyDeviceToHost));
-  for (int i = 0; i < d; ++i) {
-    uint32_t a = (uint32_t)hi[i] << 16, b = (uint32_t)lo[i] << 16;
-    float fa, fb;
-    memcpy(&fa, &a, 4);
-    memcpy(&fb, &b, 4);
-    host_hidden[i] = fa + fb;
-  }
+  // bf16 models keep the normalised activations in IEEE half: widened exactly
+  std::vector<uint16_t> hx(d);
+  TS_HIP(copy_sync(m->stream, hx.data(), (const f16_t*)m->Xn + (size_t)row * d, (size_t)d * 2, hipMemcpyDeviceToHost));
+  for (int i = 0; i < d; ++i) host_hidden[i] = half_bits_to_float(hx[i]);
   return TS_OK;
 }
 

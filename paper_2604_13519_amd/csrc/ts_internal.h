@@ -9,6 +9,7 @@
 #include "../../include/toolspec.h"
 
 typedef uint16_t bf16_t;   // bfloat16 bit pattern in memory
+typedef uint16_t f16_t;    // IEEE half bit pattern in memory
 
 // ---- error plumbing -----------------------------------------------------------
 ts_status ts_fail(ts_status code, const char* fmt, ...);
@@ -69,7 +70,7 @@ struct ts_kv {
 };
 
 struct LayerW {
-  void* wqkv; void* wo; void* wgu; void* wd;   // device; bf16: MFMA-tiled, f32: row-major [N][K]
+  void* wqkv; void* wo; void* wgu; void* wd;   // device; bf16 models: MFMA-tiled IEEE half, f32: row-major [N][K]
   float* norm1; float* norm2;                  // device fp32
 };
 
@@ -82,14 +83,15 @@ struct ts_model {
   void* embed;                  // device [V][d] in storage dtype, row-major
   void* lm_head;                // device, tiled (bf16) or row-major (f32)
   float* norm_f;
+  int* range_flag;              // device; set by the weight re-tiling when a weight does not fit IEEE half
   std::vector<LayerW> layers;
   // workspace, sized for ws_rows rows (multiple of TS_MROWS_PER_BLOCK)
   int ws_rows, ws_seqs;
   float* H;                     // residual stream [rows][d] fp32
-  void* Xn;                     // normalised activations [rows][d]; bf16 models: [2][rows][d] hi/lo planes
+  void* Xn;                     // normalised activations [rows][d]; float, or IEEE half for bf16 models
   void* Qb;                     // rotated queries [rows][q_dim]; float, or IEEE half for bf16 models
-  void* Ab;                     // attention output [rows][q_dim]; bf16 models: hi/lo planes
-  void* Fb;                     // SwiGLU product [rows][F]; bf16 models: hi/lo planes
+  void* Ab;                     // attention output [rows][q_dim]; float, or IEEE half for bf16 models
+  void* Fb;                     // SwiGLU product [rows][F]; float, or IEEE half for bf16 models
   float* part;                  // split-K partial sums, [S][rows][N] fp32
   size_t part_elems;
   uint16_t* attn_part_o;        // [splits][rows][Hq][hd], IEEE half (each split's normalised output)
@@ -114,7 +116,8 @@ struct ts_model {
 
 // ---- launchers (each defined next to its kernel) ----------------------------------
 // misc kernels (ts_kernels_misc.hip)
-void launch_repack_tiles(hipStream_t s, const bf16_t* src, bf16_t* dst, int N, int K, int n_tile0, int n_tile_stride);
+void launch_repack_tiles(hipStream_t s, const bf16_t* src, f16_t* dst, int N, int K, int n_tile0, int n_tile_stride,
+                         int* range_flag);
 void launch_embed(ts_model* m, const RowMeta& rm, int R);
 void launch_rope_table(ts_model* m, const RowMeta& rm, int R);
 void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part_stride, bool first);
@@ -136,19 +139,16 @@ struct GemmPlan { int shape; int splits; };   // compiled tile shape id, K split
 GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode);
 int gemm_bf16_cols_per_group(int shape);
 int gemm_bf16_chunk(int shape);
-void launch_gemm_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K,
-                      GemmPlan plan, int mode, float* logits, bf16_t* act_out);
+void launch_gemm_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, int R, int N, int K,
+                      GemmPlan plan, int mode, float* logits, f16_t* act_out);
 // many-row projection (ts_gemm_rows_bf16.hip), reached through gemm_bf16_plan / launch_gemm_bf16 when R > 80
 bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max_part_elems, int* mt, int* cfg, int* splits);
 int gemm_rows_chunk(int cfg);
-void launch_gemm_rows_bf16(ts_model* m, const bf16_t* X, const bf16_t* Wt, float* out, int R, int N, int K, int mt, int cfg,
-                           int splits, int mode, bf16_t* act_out);
+void launch_gemm_rows_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, int R, int N, int K, int mt, int cfg,
+                           int splits, int mode, f16_t* act_out);
 int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs, long sum_keys);
 void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int layer, int splits, int max_M);
 void launch_attn_merge(ts_model* m, int R, int splits);
-
-// element offset between the hi and lo planes of a projection input with K columns
-inline size_t act_plane(const ts_model* m, int K) { return (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * K; }
 
 // profiling bracket
 void prof_begin(ts_model* m, const char* name);

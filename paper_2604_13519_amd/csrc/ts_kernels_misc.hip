@@ -12,31 +12,31 @@
 __device__ __forceinline__ void st_q(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st_q(bf16_t* p, float v) { *p = f32_to_f16_bits(v); }
 
-// store an activation that feeds a projection: float as is, bf16 as a (hi, lo) pair of planes
-__device__ __forceinline__ void st_act(float* p, size_t, float v) { *p = v; }
-__device__ __forceinline__ void st_act(bf16_t* p, size_t lo_plane, float v) { split_bf16(v, p[0], p[lo_plane]); }
-// four consecutive activations (p 16-byte aligned in float terms): one vector store per plane
-__device__ __forceinline__ void st_act4(float* p, size_t, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
-__device__ __forceinline__ void st_act4(bf16_t* p, size_t lo_plane, const float4& v) {
-  bf16_t hi[4], lo[4];
-  split_bf16(v.x, hi[0], lo[0]); split_bf16(v.y, hi[1], lo[1]);
-  split_bf16(v.z, hi[2], lo[2]); split_bf16(v.w, hi[3], lo[3]);
-  *reinterpret_cast<uint2*>(p) = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-  *reinterpret_cast<uint2*>(p + lo_plane) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+// store an activation that feeds a projection: float as is, IEEE half (saturating) for bf16 models
+__device__ __forceinline__ void st_act(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_act(f16_t* p, float v) { *p = f32_to_f16_sat(v); }
+// four consecutive activations (p 16-byte aligned in float terms): one vector store
+__device__ __forceinline__ void st_act4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st_act4(f16_t* p, const float4& v) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack_f16x2_sat(v.x, v.y), pack_f16x2_sat(v.z, v.w));
 }
 
 // ---------------------------------------------------------------------------------
-// weight re-tiling (model load): row-major [N][K] bf16 -> MFMA operand tiles.
+// weight re-tiling (model load): row-major [N][K] bf16 -> MFMA operand tiles of IEEE half.
 // Tile (nt, kt) covers out-features [16 nt, 16 nt + 16) x in-features [32 kt, 32 kt + 32)
 // and is stored as 64 lanes x 8 elements, lane l holding W[16 nt + l%16][32 kt + 8 (l/16) + e],
 // i.e. exactly one wave-wide 16-byte-per-lane load.  Tiles of one nt are contiguous in kt.
 // Destination tile index = n_tile0 + nt * n_tile_stride, which lets two matrices be
 // interleaved tile by tile (gate / up).  Rows >= N are zero-filled.
+// bf16 -> half is exact wherever half is normal (8 significand bits into 11); magnitudes below
+// 2^-14 round to half's subnormal grid (absolute error below 3e-8).  A finite weight beyond
+// half's range (> 65504) cannot be represented: *range_flag is set and the load fails.
 // ---------------------------------------------------------------------------------
-__global__ void k_repack_tiles(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
-                               int N, int K, int n_tile0, int n_tile_stride) {
+__global__ void k_repack_tiles(const bf16_t* __restrict__ src, f16_t* __restrict__ dst,
+                               int N, int K, int n_tile0, int n_tile_stride, int* __restrict__ range_flag) {
   const int kt_count = K / 32;
   const size_t n_tiles = (size_t)((N + 15) / 16) * kt_count;
+  bool bad = false;
   for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < n_tiles * 64;
        v += (size_t)gridDim.x * blockDim.x) {
     const int lane = (int)(v & 63);
@@ -46,17 +46,26 @@ __global__ void k_repack_tiles(const bf16_t* __restrict__ src, bf16_t* __restric
     const int k = kt * 32 + (lane >> 4) * 8;
     uint4 val = make_uint4(0, 0, 0, 0);
     if (n < N) val = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);
+    const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float a = __uint_as_float(w[i] << 16), b = __uint_as_float(w[i] & 0xffff0000u);
+      bad |= (fabsf(a) > 65504.f && fabsf(a) < INFINITY) || (fabsf(b) > 65504.f && fabsf(b) < INFINITY);
+      o[i] = pack_f16x2(a, b);
+    }
     const size_t dtile = (size_t)(n_tile0 + nt * n_tile_stride) * kt_count + kt;
-    *reinterpret_cast<uint4*>(dst + (dtile * 64 + lane) * 8) = val;
+    *reinterpret_cast<uint4*>(dst + (dtile * 64 + lane) * 8) = make_uint4(o[0], o[1], o[2], o[3]);
   }
+  if (bad) atomicOr(range_flag, 1);
 }
 
-void launch_repack_tiles(hipStream_t s, const bf16_t* src, bf16_t* dst, int N, int K, int n_tile0,
-                         int n_tile_stride) {
+void launch_repack_tiles(hipStream_t s, const bf16_t* src, f16_t* dst, int N, int K, int n_tile0,
+                         int n_tile_stride, int* range_flag) {
   size_t vecs = (size_t)((N + 15) / 16) * (K / 32) * 64;
   int blocks = (int)((vecs + 255) / 256);
   if (blocks > 65535) blocks = 65535;
-  hipLaunchKernelGGL(k_repack_tiles, dim3(blocks), dim3(256), 0, s, src, dst, N, K, n_tile0, n_tile_stride);
+  hipLaunchKernelGGL(k_repack_tiles, dim3(blocks), dim3(256), 0, s, src, dst, N, K, n_tile0, n_tile_stride, range_flag);
 }
 
 // ---------------------------------------------------------------------------------
@@ -98,14 +107,14 @@ void launch_rope_table(ts_model* m, const RowMeta& rm, int R) {
 
 // ---------------------------------------------------------------------------------
 // residual update + RMSNorm:  H[r] += sum_s part[s][r]  (skipped when n_parts = 0),
-// Xn[r] = H[r] * rsqrt(mean(H[r]^2) + eps) * gain, stored as float (fp32 models) or as a
-// (hi, lo) pair of bf16 planes (bf16 models: every projection input is such a pair).
+// Xn[r] = H[r] * rsqrt(mean(H[r]^2) + eps) * gain, stored as float (fp32 models) or as IEEE
+// half (bf16 models: every projection input is a half).
 // One block of 1024 threads per row, 16-byte accesses; needs d_model % 4 == 0.
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const float* __restrict__ part, int n_parts,
                                                size_t part_stride, const float* __restrict__ gain,
-                                               T* __restrict__ Xn, size_t lo_plane, int d, float eps) {
+                                               T* __restrict__ Xn, int d, float eps) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   float4* h4 = reinterpret_cast<float4*>(H + (size_t)r * d);
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
   for (int w = 0; w < 16; ++w) tot += red[w];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
   auto emit = [&](int i, const float4& v, const float4& g) {
-    st_act4(Xn + (size_t)r * d + 4 * i, lo_plane, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
+    st_act4(Xn + (size_t)r * d + 4 * i, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
   };
 #pragma unroll
   for (int k = 0; k < KEEP; ++k) {
@@ -162,11 +171,11 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
 void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part_stride, bool) {
   ProfScope ps(m, "residual_rmsnorm");
   if (m->cfg.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_norm<bf16_t>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (bf16_t*)m->Xn, act_plane(m, m->cfg.d_model), m->cfg.d_model, m->cfg.rms_eps);
+    hipLaunchKernelGGL(k_norm<f16_t>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
+                       (f16_t*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
   else
     hipLaunchKernelGGL(k_norm<float>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (float*)m->Xn, (size_t)0, m->cfg.d_model, m->cfg.rms_eps);
+                       (float*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
 }
 
 // ---------------------------------------------------------------------------------
@@ -241,7 +250,7 @@ void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_part
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t part_stride, T* __restrict__ Fb,
-                         size_t lo_plane, int R, int F) {
+                         int R, int F) {
   const size_t total = (size_t)R * F;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int r = (int)(i / F), f = (int)(i % F);
@@ -252,7 +261,7 @@ __global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t par
       g += p[(size_t)s * part_stride];
       u += p[(size_t)s * part_stride + 16];
     }
-    st_act(Fb + i, lo_plane, g / (1.0f + expf(-g)) * u);
+    st_act(Fb + i, g / (1.0f + expf(-g)) * u);
   }
 }
 
@@ -263,9 +272,9 @@ void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride) {
   int blocks = (int)((total + 255) / 256);
   if (blocks > 4096) blocks = 4096;
   if (m->cfg.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_swiglu<bf16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (bf16_t*)m->Fb, act_plane(m, F), R, F);
+    hipLaunchKernelGGL(k_swiglu<f16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (f16_t*)m->Fb, R, F);
   else
-    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, (size_t)0, R, F);
+    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, R, F);
 }
 
 // ---------------------------------------------------------------------------------

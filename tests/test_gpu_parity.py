@@ -353,6 +353,21 @@ def test_many_row_projection_row_counts(cfg_name, total_rows):
 # ------------------------------------------------------------------------------------
 # boundary: error paths (forced from the host; every kernel still exits normally)
 # ------------------------------------------------------------------------------------
+def test_weight_beyond_half_range_fails_the_load():
+    """bf16 models multiply in IEEE half: a finite weight that half cannot hold (|w| > 65504) must
+    make ts_model_load fail instead of becoming an infinity; the largest finite half still loads."""
+    cfg = wl.get_config("small_bf16_hd64")
+    w = wl.gen_weights(cfg, 77)
+    w["layers"][1]["wo"] = w["layers"][1]["wo"].copy()
+    w["layers"][1]["wo"][3, 5] = 0x4780            # bf16 bits of 65536.0
+    with pytest.raises(B.TsError) as e:
+        B.ts_model_load(cfg, w)
+    assert e.value.status == B.TS_ERR_INVALID_ARG, str(e.value)
+    w["layers"][1]["wo"][3, 5] = 0x477F            # 65280.0, representable
+    model = B.ts_model_load(cfg, w)
+    B.ts_model_free(model)
+
+
 def test_error_paths_leave_state_untouched():
     cfg, w, model, omodel = U.get_model("micro_fp32")
     kv = B.ts_kv_alloc(model, 40)
