@@ -109,7 +109,7 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   f16x8 w[NBUF][NT][KSW];
-  u32x4 xr[XPT];
+  u32x4 xr[NBUF][XPT];   // activation chunks travel the same register ring as the weights
 
   auto load_w = [&](f16x8 (&dst)[NT][KSW], int chunk) {
 #pragma unroll
@@ -119,16 +119,16 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
         dst[t][j] = __builtin_nontemporal_load(
             reinterpret_cast<const f16x8*>(wbase[t] + (size_t)chunk * (KSTEPS * 1024) + w_lane + j * 1024));
   };
-  auto load_x = [&](int chunk) {
+  auto load_x = [&](u32x4 (&dst)[XPT], int chunk) {
     const char* xb = xbase + (size_t)chunk * (KC * 2);
 #pragma unroll
-    for (int p = 0; p < XPT; ++p) xr[p] = *reinterpret_cast<const u32x4*>(xb + x_off[p]);   // never predicated, see below
+    for (int p = 0; p < XPT; ++p) dst[p] = *reinterpret_cast<const u32x4*>(xb + x_off[p]);   // never predicated, see below
   };
-  auto store_x = [&](int buf) {
+  auto store_x = [&](const u32x4 (&src)[XPT], int buf) {
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
-      if (XV % NTHR == 0 || v < XV) *reinterpret_cast<u32x4*>(&xs[buf][v / (KC / 8)][(v % (KC / 8)) * 8]) = xr[p];
+      if (XV % NTHR == 0 || v < XV) *reinterpret_cast<u32x4*>(&xs[buf][v / (KC / 8)][(v % (KC / 8)) * 8]) = src[p];
     }
   };
   auto mma_chunk = [&](const f16x8 (&wc)[NT][KSW], int buf) {
@@ -148,41 +148,44 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
 
   // Vector-memory loads complete in issue order as far as the wait counter is concerned, and
   // the compiler's wait for a load counts every later load that MIGHT not have been issued as
-  // not issued.  Two consequences shape this loop: the small X loads are issued BEFORE the
-  // weight prefetch of the same step (waiting for X then leaves the newest weights in flight),
-  // and the steady-state trips issue both unconditionally - a prefetch under an `if` would
-  // turn every wait for X into a wait for all weights as well.  The last chunks, where
-  // there is nothing left to prefetch, run in a predicated tail.
-  auto step = [&](f16x8 (&wcur)[NT][KSW], f16x8 (&wnext)[NT][KSW], int c, bool steady) {
-    const bool more = steady || c + 1 < n_chunks;
-    if (more) load_x(c + 1);
-    __builtin_amdgcn_sched_barrier(0);      // X loads first, then the weight prefetch
-    if (steady || c + PF < n_chunks) load_w(wnext, c + PF);
+  // not issued.  Three consequences shape this loop.  The activation chunk of step c + PF is
+  // requested together with the weights of step c + PF and waits in registers as long as they
+  // do: were it requested one step ahead, storing it to LDS would first wait for every weight
+  // load issued before it, and the weights would never be more than one step ahead either.  The
+  // small X loads go out BEFORE the weight loads of the same step.  And no load is ever
+  // predicated - a prefetch under an `if` would turn every wait into a wait for everything;
+  // where nothing is left to prefetch the step re-requests the last chunk instead (an L2 hit
+  // that is never used).
+  const int last = n_chunks - 1;
+  auto step = [&](f16x8 (&wcur)[NT][KSW], f16x8 (&wpf)[NT][KSW], u32x4 (&xpf)[XPT], const u32x4 (&xnext)[XPT], int c) {
+    load_x(xpf, min(c + PF, last));
+    __builtin_amdgcn_sched_barrier(0);
+    load_w(wpf, min(c + PF, last));
     __builtin_amdgcn_sched_barrier(0);
     mma_chunk(wcur, c & 1);
-    if (more) store_x((c + 1) & 1);
+    store_x(xnext, (c + 1) & 1);            // chunk c + 1, requested PF - 1 steps ago
     __syncthreads();
   };
 
-  load_x(0);
-  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int b = 0; b < PF; ++b)
-    if (b < n_chunks) load_w(w[b], b);
-  store_x(0);
+  for (int b = 0; b < PF; ++b) {
+    load_x(xr[b], min(b, last));
+    __builtin_amdgcn_sched_barrier(0);
+    load_w(w[b], min(b, last));
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  store_x(xr[0], 0);
   __syncthreads();
 
   // NBUF chunks per trip so that ring slots are compile-time register names
   int c0 = 0;
-  for (; c0 + NBUF + PF <= n_chunks; c0 += NBUF) {
+  for (; c0 + NBUF <= n_chunks; c0 += NBUF) {
 #pragma unroll
-    for (int b = 0; b < NBUF; ++b) step(w[b], w[(b + PF) % NBUF], c0 + b, true);
+    for (int b = 0; b < NBUF; ++b) step(w[b], w[(b + PF) % NBUF], xr[(b + PF) % NBUF], xr[(b + 1) % NBUF], c0 + b);
   }
-  for (; c0 < n_chunks; c0 += NBUF) {
 #pragma unroll
-    for (int b = 0; b < NBUF; ++b)
-      if (c0 + b < n_chunks) step(w[b], w[(b + PF) % NBUF], c0 + b, false);
-  }
+  for (int b = 0; b < NBUF - 1; ++b)
+    if (c0 + b < n_chunks) step(w[b], w[(b + PF) % NBUF], xr[(b + PF) % NBUF], xr[(b + 1) % NBUF], c0 + b);
 
   if (!ARGMAX) {
     // value of output (row tile mt, row r of the lane group, tile t) goes to memory
