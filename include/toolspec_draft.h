@@ -99,6 +99,33 @@ ts_status ts_drafter_state(const ts_drafter* d, int32_t* state, int32_t* tool, i
 ts_status ts_drafter_draft(ts_drafter* d, int32_t max_nodes, int32_t* draft_tokens, int32_t* parent_idx,
                            int32_t* n_nodes, int32_t* source);
 
+/* Counters of one ts_generate call. */
+typedef struct {
+  int32_t steps;             /* target passes (Alg. 1 iterations)                                  */
+  int32_t drafted_nodes;     /* draft-tree nodes verified, summed over the steps                   */
+  int32_t accepted_tokens;   /* accepted draft tokens (the bonus token of each step not counted)   */
+  int32_t retrieval_steps;   /* steps whose tree came from SuffixMatch                             */
+  int32_t schema_steps;      /* ... from SchemaAwareDraft                                          */
+  int32_t plain_steps;       /* steps with no draft (vanilla decoding)                             */
+  int32_t stop_index;        /* index in out_tokens of the first stop_token, -1 if none            */
+  double draft_seconds;      /* host time in ts_drafter_draft                                      */
+  double verify_seconds;     /* time in ts_verify + ts_kv_commit (device work included)            */
+} ts_generate_stats;
+
+/* Alg. 1, the whole loop: repeat { draft tree <- ts_drafter_draft; (l, tokens, bonus) <- ts_verify;
+ * ts_kv_commit; y <- y (+) tokens (+) bonus; q <- delta(q, .) } until at least max_new_tokens are
+ * out or a step emitted stop_token (stop_token < 0: never).  Before the call the cache holds the
+ * context with its last token pending (ts_prefill leaves it so) and the drafter has been reset
+ * (and, for retrieval drafts, given its calls).  A step is never cut short: n_out may exceed
+ * max_new_tokens by up to TS_MAX_NODES, so out_tokens needs max_new_tokens + TS_MAX_NODES + 1
+ * ints; every emitted token is in the cache and in the drafter's y afterwards.  When the cache
+ * has no room left for a tree the step falls back to plain decoding (no draft); when it has no
+ * room for one more row the call returns KV_CAPACITY with everything emitted so far reported.
+ * Greedy acceptance; the emitted stream is the target's own greedy stream (Sec. 5.1).
+ * stats may be NULL.  Errors of the calls it makes are returned as they are. */
+ts_status ts_generate(ts_model* m, ts_kv* kv, ts_drafter* d, int32_t max_new_tokens, int32_t stop_token,
+                      int32_t* out_tokens, int32_t* n_out, ts_generate_stats* stats);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,13 +25,19 @@ EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_log
            "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_sample", "ts_verify_batch",
            "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read",
            "ts_drafter_create", "ts_drafter_free", "ts_drafter_retrieve", "ts_drafter_reset",
-           "ts_drafter_append", "ts_drafter_state", "ts_drafter_draft")
+           "ts_drafter_append", "ts_drafter_state", "ts_drafter_draft", "ts_generate")
 
 
 class TsError(RuntimeError):
     def __init__(self, status, message):
         super().__init__("toolspec status %d: %s" % (status, message))
         self.status = status
+
+
+class ts_generate_stats(C.Structure):
+    _fields_ = [("steps", C.c_int32), ("drafted_nodes", C.c_int32), ("accepted_tokens", C.c_int32),
+                ("retrieval_steps", C.c_int32), ("schema_steps", C.c_int32), ("plain_steps", C.c_int32),
+                ("stop_index", C.c_int32), ("draft_seconds", C.c_double), ("verify_seconds", C.c_double)]
 
 
 class ts_model_config(C.Structure):
@@ -112,6 +118,7 @@ def load_library(path=None):
         "ts_drafter_append": [C.c_void_p, i32p, C.c_int32],
         "ts_drafter_state": [C.c_void_p, i32p, i32p, i32p],
         "ts_drafter_draft": [C.c_void_p, C.c_int32, i32p, i32p, i32p, i32p],
+        "ts_generate": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, i32p, i32p, C.POINTER(ts_generate_stats)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -390,6 +397,15 @@ def ts_drafter_state(drafter):
     s, t, n = C.c_int32(), C.c_int32(), C.c_int32()
     _check(load_library().ts_drafter_state(drafter, C.byref(s), C.byref(t), C.byref(n)))
     return s.value, t.value, n.value
+
+
+def ts_generate(model, kv, drafter, max_new_tokens, stop_token=-1):
+    """The decoding loop of the method as one native call.  Returns (tokens, stats dict)."""
+    out = np.zeros(max_new_tokens + TS_MAX_NODES + 1, np.int32)
+    n = C.c_int32()
+    st = ts_generate_stats()
+    _check(load_library().ts_generate(model, kv, drafter, max_new_tokens, stop_token, _ptr_i32(out), C.byref(n), C.byref(st)))
+    return out[:n.value].tolist(), {f: getattr(st, f) for f, _ in ts_generate_stats._fields_}
 
 
 def ts_drafter_draft(drafter, max_nodes=TS_MAX_NODES):

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libtoolspec_hip.so")
-SOURCES = ["ts_host.hip", "ts_kernels_misc.hip", "ts_gemm_bf16.hip", "ts_gemm_rows_bf16.hip", "ts_attn_bf16.hip", "ts_draft.cpp"]
+SOURCES = ["ts_host.hip", "ts_kernels_misc.hip", "ts_gemm_bf16.hip", "ts_gemm_rows_bf16.hip", "ts_attn_bf16.hip", "ts_draft.cpp", "ts_generate.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # keep hipcc from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -76,6 +76,24 @@ def test_alg1_loop_is_lossless_and_accelerates(cfg_name):
         assert {1, 2, 3} <= {DO.fsm_replay(schema, out[:i])[0] for i in range(1, len(out) + 1)}
         assert states <= {0, 1, 2, 3}
         U._stat("%s Alg. 1 loop: %d tokens in %d target passes" % (cfg_name, len(out), passes))
+        # the same loop as one native call: same stream, same number of passes
+        kv2 = B.ts_kv_alloc(model, len(prompt) + n_new + 80)
+        try:
+            B.ts_drafter_reset(d)
+            B.ts_prefill(model, kv2, prompt)
+            out2, st = B.ts_generate(model, kv2, d, n_new)
+            assert out2 == out and st["steps"] == passes, (st, passes)
+            assert st["retrieval_steps"] > 0 and st["schema_steps"] > 0 and st["stop_index"] == -1
+            assert st["accepted_tokens"] == len(out) - passes
+            assert B.ts_kv_len(kv2) == len(prompt) - 1 + len(out2)
+            # a stop token ends the loop after the step that emits it
+            B.ts_drafter_reset(d)
+            B.ts_kv_truncate(kv2, len(prompt) - 1)
+            B.ts_set_pending(kv2, int(prompt[-1]))
+            out3, st3 = B.ts_generate(model, kv2, d, n_new, stop_token=out[10])
+            assert st3["stop_index"] == out.index(out[10]) and out3 == out[:len(out3)] and len(out3) < len(out)
+        finally:
+            B.ts_kv_free(kv2)
     finally:
         B.ts_kv_free(kv)
         B.ts_drafter_free(d)
