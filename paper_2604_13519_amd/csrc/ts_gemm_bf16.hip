@@ -340,7 +340,7 @@ int gemm_bf16_chunk(int shape) { return shape >= kRowsShape0 ? gemm_rows_chunk((
 // overlap), which the round count models.  mode: 0 partial sums, 1 arg-max (no split),
 // 2 SwiGLU epilogue (no split).
 GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
-  if (R > TS_MROWS_PER_BLOCK && mode != MODE_ARGMAX) {   // batches: the many-row kernel
+  if (R > TS_MROWS_PER_BLOCK) {   // batches: the many-row kernel
     int mt, cfg, splits;
     const size_t max_part = m->part_elems ? m->part_elems : kRowsPartCap;
     if (gemm_rows_plan(m, R, N, K, mode, max_part, &mt, &cfg, &splits)) return GemmPlan{kRowsShape0 + mt * 4 + cfg, splits};
@@ -377,7 +377,7 @@ void launch_gemm_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, 
                       int mode, float* logits, f16_t* act_out) {
   if (plan.shape >= kRowsShape0) {
     const int code = plan.shape - kRowsShape0;
-    launch_gemm_rows_bf16(m, X, Wt, out, R, N, K, code / 4, code % 4, plan.splits, mode, act_out);
+    launch_gemm_rows_bf16(m, X, Wt, out, R, N, K, code / 4, code % 4, plan.splits, mode, act_out, logits);
     return;
   }
   GemmArgs a;
@@ -391,6 +391,7 @@ void launch_gemm_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, 
   a.kt_count = K / 32;
   a.split_stride = (size_t)R * N;
   a.amax_parts = m->amax_parts;
+  if (mode == MODE_ARGMAX) m->amax_used = (N + gemm_bf16_cols_per_group(plan.shape) - 1) / gemm_bf16_cols_per_group(plan.shape);
   const int cols = gemm_bf16_cols_per_group(plan.shape);
   const int groups = (N + cols - 1) / cols;
   const int m_blocks = (R + TS_MROWS_PER_BLOCK - 1) / TS_MROWS_PER_BLOCK;

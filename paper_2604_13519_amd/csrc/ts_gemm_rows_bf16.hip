@@ -19,6 +19,8 @@
 //    [split][row][col] for the next row-wise kernel (deterministic, no atomics).
 //  * gate/up variant (SWIGLU): gate and up tiles alternate, a wave holds two (gate, up) pairs
 //    and the epilogue stores SiLU(gate) * up as half.
+//  * lm_head variant (ARGMAX, 8x1 only, no K split): the epilogue reduces each row's maximum over
+//    the workgroup's 512 columns and emits one (value, index) partial per row and column group.
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 #include <algorithm>
@@ -35,6 +37,10 @@ struct RowsArgs {
   const f16_t* Wt;     // tiled weights, IEEE half
   float* out;          // [split][R][N] partial sums
   f16_t* act_out;      // SWIGLU: [x_rows][N/2] IEEE half
+  float* logits;       // ARGMAX: [R][N] or nullptr
+  float* aval;         // ARGMAX: [R][amax_stride] partial maxima, one per column group
+  int32_t* aidx;
+  int amax_stride;
   int R, N, K;
   int kper;            // k elements per split
   int n_tiles;         // ceil(N / 16)
@@ -45,13 +51,14 @@ struct RowsArgs {
   int n_rblocks;       // row blocks
 };
 
-enum { MODE_PARTIAL = 0, MODE_SWIGLU = 2 };
+enum { MODE_PARTIAL = 0, MODE_ARGMAX = 1, MODE_SWIGLU = 2 };
 constexpr int NT = 4;        // tiles of 16 output features per wave
 constexpr int WAVES = 8;
 
 template <int MT, int CS, int KW, int MODE>
 __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
   static_assert(CS * KW == WAVES, "8 waves");
+  static_assert(MODE != MODE_ARGMAX || KW == 1, "the arg-max epilogue expects one wave per column set");
   constexpr int KC = KW * 32;             // k elements per staged chunk: one k-step per wave
   constexpr int KSTEPS = KC / 32;
   constexpr int KSW = KSTEPS / KW;          // k-steps of a chunk this wave multiplies
@@ -62,7 +69,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
   constexpr int XPT = (XV + NTHR - 1) / NTHR;
   constexpr size_t XS_BYTES = sizeof(f16_t) * 2 * MT * 16 * XS;
   constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * 4 * NT * 64 : 0;   // the reduction reuses the activation buffers
-  __shared__ __attribute__((aligned(16))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
+  constexpr size_t AMAX_BYTES = MODE == MODE_ARGMAX ? (size_t)8 * WAVES * MT * 16 : 0;
+  constexpr size_t SMEM_BYTES = XS_BYTES > RED_BYTES ? (XS_BYTES > AMAX_BYTES ? XS_BYTES : AMAX_BYTES) : (RED_BYTES > AMAX_BYTES ? RED_BYTES : AMAX_BYTES);
+  __shared__ __attribute__((aligned(16))) char smem[SMEM_BYTES];
   f16_t (*xs)[MT * 16][XS] = reinterpret_cast<f16_t (*)[MT * 16][XS]>(smem);
 
   // place: XCD = blockIdx.x % 8; the row blocks of a weight slab follow each other on one XCD
@@ -160,6 +169,46 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
     if (c0 + 1 < n_chunks) step(w[1], w[0], c0 + 1, false);
   }
 
+  if (MODE == MODE_ARGMAX) {
+    // per row: maximum over the wave's 64 columns (in-lane over the 4 tiles, then over the 16
+    // lanes of the row), then over the 8 waves through LDS (free after the loop's last barrier)
+    float* rv = reinterpret_cast<float*>(smem);                    // [WAVES][MT * 16]
+    int* ri = reinterpret_cast<int*>(smem) + WAVES * MT * 16;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = row0 + mt * 16 + g * 4 + r;
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const int col = nt_idx[t] * 16 + l15;
+          if (nt_idx[t] < a.n_tiles && col < a.N) {
+            const float v = acc[mt][t][r];
+            if (a.logits != nullptr && row < a.R) a.logits[(size_t)row * a.N + col] = v;
+            amax_take(bv, bi, v, col);
+          }
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {
+          const float ov = __shfl_xor(bv, o, 64);
+          const int oi = __shfl_xor(bi, o, 64);
+          amax_take(bv, bi, ov, oi);
+        }
+        if (l15 == 0) { rv[wave * (MT * 16) + mt * 16 + g * 4 + r] = bv; ri[wave * (MT * 16) + mt * 16 + g * 4 + r] = bi; }
+      }
+    __syncthreads();
+    if (tid < MT * 16 && row0 + tid < a.R) {
+      float bv = rv[tid];
+      int bi = ri[tid];
+      for (int wv = 1; wv < WAVES; ++wv) amax_take(bv, bi, rv[wv * (MT * 16) + tid], ri[wv * (MT * 16) + tid]);
+      a.aval[(size_t)(row0 + tid) * a.amax_stride + group] = bv;
+      a.aidx[(size_t)(row0 + tid) * a.amax_stride + group] = bi;
+    }
+    return;
+  }
+
   // value of output (row tile mt, row r of the lane group, tile t) goes to memory
   auto emit = [&](int mt, int r, const float (&v)[NT]) {
     const int row = row0 + mt * 16 + g * 4 + r;
@@ -230,10 +279,14 @@ const int kCfgKC[kNumCfg] = {32, 64, 128};
 template <int MT, int MODE>
 void launch_cfg(int cfg, dim3 grid, hipStream_t s, const RowsArgs& a) {
   const dim3 block(64 * WAVES);
+  if (MODE == MODE_ARGMAX) {                      // 8x1 only
+    hipLaunchKernelGGL((k_gemm_rows_bf16<MT, 8, 1, MODE>), grid, block, 0, s, a);
+    return;
+  }
   switch (cfg) {
     case 0: hipLaunchKernelGGL((k_gemm_rows_bf16<MT, 8, 1, MODE>), grid, block, 0, s, a); break;
-    case 1: hipLaunchKernelGGL((k_gemm_rows_bf16<MT, 4, 2, MODE>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((k_gemm_rows_bf16<MT, 2, 4, MODE>), grid, block, 0, s, a); break;
+    case 1: hipLaunchKernelGGL((k_gemm_rows_bf16<MT, 4, 2, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((k_gemm_rows_bf16<MT, 2, 4, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>), grid, block, 0, s, a); break;
   }
 }
 
@@ -266,6 +319,7 @@ bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max
     const int n_rblocks = (tiles + mt - 1) / mt;
     if (mt > kMinMT && n_rblocks == (tiles + mt - 2) / (mt - 1)) continue;   // same blocks, more idle rows
     for (int cfg = 0; cfg < kNumCfg; ++cfg) {
+      if (mode == MODE_ARGMAX && cfg != 0) break;
       const int kc = kCfgKC[cfg];
       if (K % kc) continue;
       const int chunks = K / kc;
@@ -295,11 +349,12 @@ bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max
 }
 
 void launch_gemm_rows_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, int R, int N, int K, int mt, int cfg,
-                           int splits, int mode, f16_t* act_out) {
+                           int splits, int mode, f16_t* act_out, float* logits) {
   RowsArgs a;
   a.x_rows = m->ws_rows + TS_MROWS_PER_BLOCK;
   a.X = X; a.Wt = Wt; a.out = out;
   a.act_out = act_out;
+  a.logits = logits; a.aval = m->amax_val; a.aidx = m->amax_idx; a.amax_stride = m->amax_parts;
   a.R = R; a.N = N; a.K = K;
   if (mode != MODE_PARTIAL) splits = 1;
   a.kper = K / splits;
@@ -311,6 +366,8 @@ void launch_gemm_rows_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* 
   a.n_units = a.n_groups * splits;
   a.n_rblocks = ((R + 15) / 16 + mt - 1) / mt;
   dim3 grid((unsigned)((a.n_units + 7) / 8) * 8 * a.n_rblocks);
+  if (mode == MODE_ARGMAX) m->amax_used = a.n_groups;       // partials the combine kernel has to look at
   if (mode == MODE_SWIGLU) launch_mt<MODE_SWIGLU>(mt, cfg, grid, m->stream, a);
+  else if (mode == MODE_ARGMAX) launch_mt<MODE_ARGMAX>(mt, cfg, grid, m->stream, a);
   else launch_mt<MODE_PARTIAL>(mt, cfg, grid, m->stream, a);
 }

@@ -378,6 +378,7 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   } else {
     m->amax_parts = 1;
   }
+  m->amax_used = m->amax_parts;
   st = model_load_impl(m, w);
   if (!st) st = ensure_workspace(m, TS_MAX_NODES + 1, 1);
   if (st) {
@@ -692,7 +693,9 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   }
   launch_norm(m, R, m->norm_f, pending_parts, pending_stride, false);
   if (bf) {
-    const GemmPlan p = gemm_bf16_plan(m, TS_MROWS_PER_BLOCK, c.vocab, d, 1);   // as at load: fixes the partial count
+    // one row block: the plan made at load (it sized the partial buffers); batches: the many-row kernel,
+    // whose 512-column groups need fewer partials
+    const GemmPlan p = gemm_bf16_plan(m, std::max(R, TS_MROWS_PER_BLOCK), c.vocab, d, 1);
     ProfScope ps(m, "gemm_lm_head_argmax");
     launch_gemm_bf16(m, (const f16_t*)m->Xn, (const f16_t*)m->lm_head, nullptr, R, c.vocab, d, p, 1,
                      (m->keep_logits || sample) ? m->logits : nullptr, nullptr);

@@ -99,6 +99,7 @@ struct ts_model {
   int attn_max_splits;
   float2* rope_cs;              // [rows][hd/2] (cos, sin)
   float* amax_val; int32_t* amax_idx; int amax_parts;   // [rows][parts]
+  int amax_used;                // partials per row the last lm_head launch wrote (<= amax_parts)
   float* logits; bool keep_logits; int logits_rows;     // [rows][V] when kept
   float* samp_lse; int32_t* samp_tok;                   // per-row token (greedy arg-max or residual sample); log-sum-exp for sampling
   // per-call metadata (device + pinned host mirror)
@@ -145,7 +146,7 @@ void launch_gemm_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, 
 bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max_part_elems, int* mt, int* cfg, int* splits);
 int gemm_rows_chunk(int cfg);
 void launch_gemm_rows_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, int R, int N, int K, int mt, int cfg,
-                           int splits, int mode, f16_t* act_out);
+                           int splits, int mode, f16_t* act_out, float* logits);
 int attn_bf16_splits(const ts_model* m, int max_keys, int n_seqs, long sum_keys);
 void launch_attn_bf16(ts_model* m, const RowMeta& rm, int R, int n_seqs, int layer, int splits, int max_M);
 void launch_attn_merge(ts_model* m, int R, int splits);

@@ -384,7 +384,7 @@ __global__ __launch_bounds__(128) void k_walk(const int32_t* __restrict__ g_row,
 void launch_walk(ts_model* m, const RowMeta& rm, int R, int n_seqs) {
   ProfScope ps(m, "accept_walk");
   hipLaunchKernelGGL(k_argmax_combine, dim3(R), dim3(256), 0, m->stream, m->amax_val, m->amax_idx, m->amax_parts,
-                     m->amax_parts, m->samp_tok);
+                     m->amax_used, m->samp_tok);
   hipLaunchKernelGGL(k_walk, dim3(n_seqs), dim3(128), 0, m->stream, m->samp_tok, rm.tok, rm.par, rm.depth, m->seq_dev);
 }
 
