@@ -20,7 +20,7 @@
 //   S^T[key][query] = K . Q^T     A = K tile from LDS (16 keys x 32 dims per step)
 //                                 B = Q fragments, resident in registers
 //   lane l then holds query (l % 16) and 4 keys of each 16-key tile, so the soft-max
-//   maximum over keys is an in-lane max plus two xor-shuffles (16, 32), and the exponentials
+//   maximum over keys is an in-lane max plus two lane swaps (16, 32), and the exponentials
 //   of two 16-key tiles pack straight into the B operand of
 //   O^T[dim][query] += V^T . P^T  A = V^T tile from LDS.  V pages are stored transposed in
 //                                 the cache ([head_dim][16 tokens]) exactly for this.
@@ -257,8 +257,7 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[kt][mt][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = max_over_lane_groups(mx);
         // the running reference is a whole number (scores in log2 units): rescaling by exact
         // powers of two commutes with the bf16 rounding of the probabilities, so the result
         // does not depend on how keys are blocked or split

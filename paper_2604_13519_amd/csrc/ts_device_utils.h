@@ -63,6 +63,17 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// maximum over the four lanes l, l^16, l^32, l^48 of a wave, through the lane-swap instructions
+// of gfx950 (v_permlane16_swap / v_permlane32_swap): each leaves a lane with its own value and
+// its partner's, so two swaps and two maxima replace two LDS-routed shuffles and their waits
+__device__ __forceinline__ float max_over_lane_groups(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const uint32_t v = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
 // keep the larger value; among equal values the lower index
 __device__ __forceinline__ void amax_take(float& bv, int& bi, float v, int i) {
   if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
