@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the tree-verify step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload w3|w2|w4|dev]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload w3|w2|w4|w5|dev]
 
 A step is one pass of the whole hot path over one draft tree: ts_verify (tree ingest,
 32-layer masked forward pass, fused vocab arg-max, acceptance walk, result to host) followed
@@ -28,7 +28,9 @@ oracle, as it stands, on a bounded sample of the same workload.
 32-node tree each: 528 rows through ts_verify_batch, then one commit per request).  Its
 projections are bound by the matrix cores, so its `roofline` is for the gate/up launch against
 the dense 16-bit MFMA peak (2 x R x N x K flop);
-`step_hbm_frac` is the whole step against HBM as for the other workloads.
+`step_hbm_frac` is the whole step against HBM as for the other workloads.  --workload w5 does the
+same for the 32B-class shape at full depth (64 layers, 4 requests x 32768-token contexts, 64-node
+trees: 64 GB of weights and 34 GB of cache on the device; about a minute of set-up).
 """
 import argparse
 import json
@@ -49,7 +51,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="w3", choices=["w3", "w2", "w4", "dev"])
+    ap.add_argument("--workload", default="w3", choices=["w3", "w2", "w4", "w5", "dev"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -110,20 +112,30 @@ def cpu_baseline(wl, cfg, weights, K, V, root, tree, mean_tokens):
 
 
 def main_batched(a, wl, B, torch):
-    """w4: one step = ts_verify_batch over 16 requests + 16 commits + host roll-back."""
-    cfg = wl.get_config("llama8b")
+    """w4 / w5: one step = ts_verify_batch over all requests + one commit each + host roll-back."""
+    if a.workload == "w4":
+        cfg = wl.get_config("llama8b")
+        contexts = [int(x) for x in np.random.default_rng([2345, 4]).integers(2048, 16385, size=16)]
+        desc = "llama3-8b-shape bf16, batch 16, paged contexts U[2048,16384], 32-node BFS trees"
+        make_tree = lambda b: wl.bfs_tree([], 32, cfg.vocab, np.random.default_rng([3456, 4, b]))
+    else:
+        cfg = wl.get_config("qwen32b")
+        contexts = [32768] * 4
+        desc = "32b-class shape (64 layers, d 5120, 64/8 heads, ffn 25600) bf16, batch 4, ctx 32768, 64-node trees"
+        make_tree = lambda b: wl.schema_retrieval_tree([], cfg.vocab, np.random.default_rng([3456, 5, b]))
     weights = wl.gen_weights(cfg, 1234)
     model = B.ts_model_load(cfg, weights)
-    contexts = [int(x) for x in np.random.default_rng([2345, 4]).integers(2048, 16385, size=16)]
+    del weights
     kvs, trees, roots = [], [], []
     for b, P in enumerate(contexts):
         K, V = wl.gen_context_kv(cfg, P, seed=2345 + b)
         kv = B.ts_kv_alloc(model, P + 80)
         B.ts_kv_import(kv, K, V)
+        del K, V
         roots.append(wl.root_token(cfg.vocab, P, seed=3456 + b))
         B.ts_set_pending(kv, roots[-1])
         kvs.append(kv)
-        trees.append(wl.bfs_tree([], 32, cfg.vocab, np.random.default_rng([3456, 4, b])))
+        trees.append(make_tree(b))
         print("[bench] request %d: context %d resident" % (b, P), file=sys.stderr, flush=True)
     R = sum(len(t[0]) + 1 for t in trees)
 
@@ -158,13 +170,12 @@ def main_batched(a, wl, B, torch):
     achieved = flop / (kernels[dom]["avg_us"] * 1e-6) / 1e12
     total_bytes = 2 * cfg.streamed_params() + sum(contexts) * cfg.kv_bytes_per_token()
     out = {
-        "metric": "accepted tokens/s of single-pass tree verification (verify + commit), 8B bf16; "
+        "metric": "accepted tokens/s of single-pass tree verification (verify + commit), batched; "
                   "with verify-step latency and % of HBM roofline",
         "value": emitted / dt, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": dt / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "llama3-8b-shape bf16, batch 16, paged contexts U[2048,16384], 32-node BFS trees",
-                   "batch": 16, "rows": R, "context_total": int(sum(contexts)),
+        "config": {"workload": desc, "batch": len(contexts), "rows": R, "context_total": int(sum(contexts)),
                    "storage": "bf16 weights and K/V cache; products in IEEE half, fp32 accumulation"},
         "verify_ms": verify_ms, "mean_tokens_per_step": emitted / a.steps,
         "step_algorithmic_gb": total_bytes / 1e9,
@@ -195,7 +206,7 @@ def main():
     from paper_2604_13519_amd import binding as B
     B.load_library()
 
-    if a.workload == "w4":
+    if a.workload in ("w4", "w5"):
         return main_batched(a, wl, B, torch)
     cfg_name, P, tree_kind, desc = workload(a.workload)
     cfg = wl.get_config(cfg_name)
