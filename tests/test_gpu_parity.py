@@ -145,24 +145,33 @@ def test_speculative_stream_equals_plain_greedy_stream(cfg_name, P0):
     are compared up to the first step whose oracle top-2 margin is below 1e-2."""
     cfg, w, model, omodel = U.get_model(cfg_name)
     rng = np.random.default_rng(9)
-    K, V = wl.gen_context_kv(cfg, P0, seed=79)
     pending = 3
     n_out = 40
     cap = P0 + n_out + 80
     mode = "E" if cfg.dtype == wl.configs.DTYPE_F32 else "R"
-    okv = O.OracleKV(cfg, cap)
-    okv.import_context(K, V)
-    okv.pending = pending
-    ref, safe = [], n_out
     empty = np.zeros(0, np.int32)
-    for i in range(n_out):
-        r = O.verify(omodel, okv, empty, empty, mode)
-        O.commit(okv, r)
-        ref.append(r.bonus_token)
-        if r.margin[0] < U.MARGIN and safe == n_out:
-            safe = i
+    # random-init models have near-ties every few dozen tokens: take, among a few context seeds, the
+    # one whose greedy stream stays clear of them longest
+    best = None
+    for seed in range(79, 85):
+        K, V = wl.gen_context_kv(cfg, P0, seed=seed)
+        okv = O.OracleKV(cfg, cap)
+        okv.import_context(K, V)
+        okv.pending = pending
+        ref, safe = [], n_out
+        for i in range(n_out):
+            r = O.verify(omodel, okv, empty, empty, mode)
+            O.commit(okv, r)
+            ref.append(r.bonus_token)
+            if r.margin[0] < U.MARGIN and safe == n_out:
+                safe = i
+        if best is None or safe > best[0]:
+            best = (safe, K, V, ref)
+        if safe >= 24:
+            break
+    safe, K, V, ref = best
     if safe < 8:
-        pytest.skip("this seed's greedy stream has a near-tie at step %d" % safe)
+        pytest.skip("no context seed whose greedy stream is free of near-ties for 8 steps")
     # device, plain autoregressive (n_nodes = 0)
     kv, _ = U.make_pair(cfg, model, K, V, pending, capacity=cap)
     ar = []
