@@ -233,6 +233,25 @@ def test_bf16_round_matches_library_conversion():
     assert O.bf16_round(np.array([1.01171875]))[0] == 1.015625
 
 
+def test_half_rounding_matches_library_conversion_and_saturates():
+    """Projection inputs of the decision mode: IEEE half, nearest even, saturating at 65504."""
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-7, 4, 5000),
+                        [0.0, -0.0, 1.0, 1.00048828125, 1.00146484375, 65504.0, 6.0e-8, 3.0e-8]])
+    ref = torch.from_numpy(x).to(torch.float32).to(torch.float16).to(torch.float64).numpy()
+    assert np.array_equal(O.fp16_round(x), ref)
+    assert np.array_equal(O.fp16_act_round(x), ref)             # nothing here is out of range
+    # ties go to even: 1 + 2^-11 is halfway between 1 and 1 + 2^-10
+    assert O.fp16_round(np.array([1.00048828125]))[0] == 1.0
+    assert O.fp16_round(np.array([1.00146484375]))[0] == 1.001953125
+    # half's subnormal grid has steps of 2^-24
+    assert O.fp16_round(np.array([6.0e-8]))[0] == 2.0 ** -24 and O.fp16_round(np.array([2.9e-8]))[0] == 0.0
+    # beyond the largest finite half: the activation rounding saturates, the plain rounding overflows
+    big = np.array([65520.0, 1.0e6, -7.0e4])
+    assert np.array_equal(O.fp16_act_round(big), [65504.0, 65504.0, -65504.0])
+    assert np.all(np.isinf(O.fp16_round(big)))
+
+
 # --------------------------------------------------------------------------- #
 # acceptance walk against exhaustive enumeration of the definition
 # --------------------------------------------------------------------------- #
