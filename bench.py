@@ -282,6 +282,15 @@ def main():
     dom_only = bracketed("gemm_gate_up", n_prof)
     kernels = bracketed(None, n_prof)
     kernels["gemm_gate_up"] = dom_only["gemm_gate_up"]
+    # the same brackets around a kernel that only reads the gate/up weight tensors (one layer's per
+    # launch, layers cycled): what the memory system gives a plain streaming read of those bytes
+    B.ts_profile_filter(model, "plain_read")
+    B.ts_profile_enable(model, True)
+    plain_bytes = B.ts_profile_plain_read(model, 5 * cfg.n_layers)
+    pn, pms = B.ts_profile_read(model)["plain_read"]
+    B.ts_profile_enable(model, False)
+    B.ts_profile_filter(model, None)
+    plain_us = pms / pn * 1e3
     dom = "gemm_gate_up"
     dom_bytes = 2 * cfg.d_ffn * cfg.d_model * 2            # gate + up weights, bf16, per launch
     dom_us = kernels[dom]["avg_us"]
@@ -309,7 +318,10 @@ def main():
         "step_hbm_frac": total_bytes / (verify_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_launch": dom_bytes,
-                     "avg_us": dom_us},
+                     "avg_us": dom_us,
+                     "plain_read": {"avg_us": plain_us, "GB/s": plain_bytes / (plain_us * 1e-6) / 1e9,
+                                    "bytes_per_launch": plain_bytes, "launches": pn,
+                                    "what": "read-only kernel over the same weight tensors, same event brackets"}},
         "kernels": kernels,
     }
     if not a.no_cpu_baseline:

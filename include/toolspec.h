@@ -217,6 +217,13 @@ ts_status ts_profile_enable(ts_model* m, int32_t enable);
  * its timing is not disturbed by events around every other launch; NULL = all kinds. */
 ts_status ts_profile_filter(ts_model* m, const char* kind_or_null);
 ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_entries, int32_t* n_entries);
+/* Reference point for the projections' bandwidth figures: `launches` launches of a kernel that
+ * only reads - launch i streams the fused gate/up weight tensor of layer i mod n_layers, the
+ * bytes the largest projection of a step streams - on the model's stream, bracketed like any
+ * other kind under the name "plain_read" (profiling must be on, and the filter, if set, must
+ * name it).  The records join those of the most recent verify.  Returns after the launches
+ * have completed; bytes_per_launch (may be NULL) receives the tensor's size. */
+ts_status ts_profile_plain_read(ts_model* m, int32_t launches, uint64_t* bytes_per_launch);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,7 @@ TS_DRAFT_NONE, TS_DRAFT_RETRIEVAL, TS_DRAFT_SCHEMA = 0, 1, 2
 EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits", "ts_get_hidden",
            "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export",
            "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_sample", "ts_verify_batch",
-           "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read",
+           "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read", "ts_profile_plain_read",
            "ts_drafter_create", "ts_drafter_free", "ts_drafter_retrieve", "ts_drafter_reset",
            "ts_drafter_append", "ts_drafter_state", "ts_drafter_draft", "ts_generate")
 
@@ -110,6 +110,7 @@ def load_library(path=None):
         "ts_profile_enable": [C.c_void_p, C.c_int32],
         "ts_profile_filter": [C.c_void_p, C.c_char_p],
         "ts_profile_read": [C.c_void_p, C.POINTER(ts_profile_entry), C.c_int32, i32p],
+        "ts_profile_plain_read": [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64)],
         "ts_drafter_create": [C.POINTER(ts_schema_desc), C.POINTER(C.c_void_p)],
         "ts_drafter_free": [C.c_void_p],
         "ts_drafter_retrieve": [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_float), C.c_int32, i32p, i32p,
@@ -314,6 +315,13 @@ def ts_profile_enable(model, enable):
 
 def ts_profile_filter(model, kind=None):
     _check(load_library().ts_profile_filter(model, kind.encode() if kind else None))
+
+
+def ts_profile_plain_read(model, launches):
+    """Launches the read-only kernel over gate/up weight tensors; returns the bytes one launch reads."""
+    n = C.c_uint64()
+    _check(load_library().ts_profile_plain_read(model, int(launches), C.byref(n)))
+    return int(n.value)
 
 
 def ts_profile_read(model, max_entries=64):

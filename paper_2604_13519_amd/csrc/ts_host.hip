@@ -871,6 +871,19 @@ extern "C" ts_status ts_profile_filter(ts_model* m, const char* kind) {
   return TS_OK;
 }
 
+extern "C" ts_status ts_profile_plain_read(ts_model* m, int32_t launches, uint64_t* bytes_per_launch) {
+  if (!m || launches < 0) return ts_fail(TS_ERR_INVALID_ARG, "null model or negative launch count");
+  if (m->layers.empty()) return ts_fail(TS_ERR_STATE, "model has no layers");
+  (void)hipSetDevice(m->device);
+  const size_t bytes = (size_t)2 * m->cfg.d_ffn * m->cfg.d_model * (m->esz == 2 ? 2 : 4);
+  for (int i = 0; i < launches; ++i)
+    launch_plain_read(m, m->layers[i % m->layers.size()].wgu, bytes, (uint32_t*)m->range_flag);
+  TS_HIP(hipGetLastError());
+  TS_HIP(hipStreamSynchronize(m->stream));
+  if (bytes_per_launch) *bytes_per_launch = bytes;
+  return TS_OK;
+}
+
 extern "C" ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_entries, int32_t* n_entries) {
   if (!m || !n_entries || (max_entries > 0 && !entries)) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
   (void)hipSetDevice(m->device);

@@ -124,6 +124,7 @@ void launch_rope_table(ts_model* m, const RowMeta& rm, int R);
 void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part_stride, bool first);
 void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_parts, size_t part_stride);
 void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride);
+void launch_plain_read(ts_model* m, const void* src, size_t bytes, uint32_t* sink);
 void launch_argmax_rows(ts_model* m, int R);
 void launch_walk(ts_model* m, const RowMeta& rm, int R, int n_seqs);
 void launch_sample(ts_model* m, const RowMeta& rm, int R, int n_seqs, float temperature, uint64_t seed);

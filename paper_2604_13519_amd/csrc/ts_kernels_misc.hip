@@ -728,3 +728,30 @@ void launch_attn_f32(ts_model* m, const RowMeta& rm, int R, int, int layer, int 
                      rm.seq, rm.lrow, rm.anc, m->seq_dev, layer, c.n_q_heads, c.n_kv_heads, c.head_dim,
                      1.0f / sqrtf((float)c.head_dim));
 }
+
+// ---------------------------------------------------------------------------------
+// Plain streaming read of a weight tensor: what the memory system gives a kernel that does
+// nothing but read, on the same bytes the fused gate/up projection streams.  One workgroup per
+// CU, eight 16-byte loads in flight per thread, grid-strided (the fastest of the grids and
+// patterns tried).  The xor of the words keeps the loads alive; nothing is written unless the
+// xor hits one value in 2^32.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_plain_read(const uint4* __restrict__ p, size_t n_vec, uint32_t* __restrict__ sink) {
+  uint32_t acc = 0;
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 7 * stride < n_vec; i += 8 * stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].w;
+  }
+  for (; i < n_vec; i += stride) acc ^= p[i].x;
+  if (acc == 0x9e3779b9u) sink[0] = acc;
+}
+
+void launch_plain_read(ts_model* m, const void* src, size_t bytes, uint32_t* sink) {
+  ProfScope ps(m, "plain_read");
+  hipLaunchKernelGGL(k_plain_read, dim3(m->n_cu), dim3(256), 0, m->stream, (const uint4*)src, bytes / 16, sink);
+}

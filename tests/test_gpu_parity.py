@@ -377,6 +377,30 @@ def test_weight_beyond_half_range_fails_the_load():
     B.ts_model_free(model)
 
 
+def test_plain_read_reference_is_bracketed_and_leaves_results_alone():
+    """The read-only reference kernel of the measurement interface: records appear under its own
+    name with the tensor's size, nothing of the model changes (the next verify equals the previous)."""
+    cfg = wl.get_config("small_bf16")
+    model = B.ts_model_load(cfg, wl.gen_weights(cfg, 5))
+    kv = B.ts_kv_alloc(model, 128)
+    K, V = wl.gen_context_kv(cfg, 40, seed=6)
+    B.ts_kv_import(kv, K, V)
+    B.ts_set_pending(kv, 3)
+    tok, par = _random_tree(np.random.default_rng(8), 12, cfg.vocab)
+    before = B.ts_verify(model, kv, tok, par)
+    B.ts_profile_filter(model, "plain_read")
+    B.ts_profile_enable(model, True)
+    nbytes = B.ts_profile_plain_read(model, 2 * cfg.n_layers + 1)
+    rec = B.ts_profile_read(model)
+    B.ts_profile_enable(model, False)
+    B.ts_profile_filter(model, None)
+    assert nbytes == 2 * cfg.d_ffn * cfg.d_model * 2
+    assert list(rec) == ["plain_read"] and rec["plain_read"][0] == 2 * cfg.n_layers + 1 and rec["plain_read"][1] > 0
+    assert B.ts_verify(model, kv, tok, par) == before
+    B.ts_kv_free(kv)
+    B.ts_model_free(model)
+
+
 def test_error_paths_leave_state_untouched():
     cfg, w, model, omodel = U.get_model("micro_fp32")
     kv = B.ts_kv_alloc(model, 40)
