@@ -316,11 +316,13 @@ def main():
         "mean_tokens_per_step": emitted / a.steps,
         "step_algorithmic_gb": total_bytes / 1e9,
         "step_hbm_frac": total_bytes / (verify_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_frac_of_plain_read": total_bytes / (verify_ms * 1e-3) / (plain_bytes / (plain_us * 1e-6)),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_launch": dom_bytes,
                      "avg_us": dom_us,
                      "plain_read": {"avg_us": plain_us, "GB/s": plain_bytes / (plain_us * 1e-6) / 1e9,
                                     "bytes_per_launch": plain_bytes, "launches": pn,
+                                    "kernel_frac_of_plain_read": plain_us / dom_us,
                                     "what": "read-only kernel over the same weight tensors, same event brackets"}},
         "kernels": kernels,
     }
