@@ -162,6 +162,11 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
   // the same barriers.
   auto body = [&](auto mt_c) {
     constexpr int MT = decltype(mt_c)::value;
+    // LDS operand fragments requested ahead of the MFMAs that consume them; 0 leaves the order to
+    // the compiler (which requests a pair, waits, multiplies).  The explicit pipeline pays in the
+    // 8-wave variants with two row splits (65 rows: -4 % with 4 query heads per KV head, -9 %
+    // with 8) and loses elsewhere (+8 % at 33 rows with one row split), measured.
+    constexpr int FD = (RS == 2 && HB == 4) ? 3 : 0;
   // resident query fragments and ancestor masks of this wave's head
   f16x8 qf[MT][KSQ];
   uint64_t anc[MT];
@@ -215,19 +220,38 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
 #pragma unroll 1   // keeping the two halves rolled holds the register need at 256
     for (int k2 = 0; k2 < 2; ++k2) {
       // ---- S^T = K . Q^T -----------------------------------------------------------
+      // With FD > 0 the K fragments come from LDS through a short software pipeline, FD of them
+      // in flight ahead of the MFMAs that consume them; the scheduling barriers keep the stages
+      // in this order.
       f32x4 s[2][MT];
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) s[kt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      constexpr int NKF = 2 * KSQ;
+      static_assert(FD <= NKF && FD <= DT, "pipeline deeper than the fragment count");
+      auto k_frag = [&](int i) {
+        return *reinterpret_cast<const f16x8*>(&ks_[cur][(2 * k2 + i / KSQ) * 16 + l15][(i % KSQ) * 32 + g4 * 8]);
+      };
+      auto v_frag = [&](int dt) { return *reinterpret_cast<const f16x8*>(&vs_[cur][k2][dt * 16 + l15][g4 * 8]); };
+      f16x8 kf[NKF];
 #pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) {
-          const f16x8 ka = *reinterpret_cast<const f16x8*>(&ks_[cur][(2 * k2 + kt) * 16 + l15][ks * 32 + g4 * 8]);
+      for (int i = 0; i < FD; ++i) kf[i] = k_frag(i);
+      if (FD > 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            s[kt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qf[mt][ks], s[kt][mt], 0, 0, 0);
-        }
+      for (int i = 0; i < NKF; ++i) {
+        if (FD == 0) kf[i] = k_frag(i);
+        else if (i + FD < NKF) kf[i + FD] = k_frag(i + FD);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          s[i / KSQ][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[i], qf[mt][i % KSQ], s[i / KSQ][mt], 0, 0, 0);
+        if (FD > 0) __builtin_amdgcn_sched_barrier(0);
       }
+      // the first V^T fragments of the second product travel while the soft-max is computed
+      f16x8 vf[DT];
+#pragma unroll
+      for (int dt = 0; dt < FD; ++dt) vf[dt] = v_frag(dt);
+      if (FD > 0) __builtin_amdgcn_sched_barrier(0);
 
       // ---- mask (only blocks that reach past the committed context) ----------------------
       if (masked) {
@@ -287,13 +311,15 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
         const f32x4 ps = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.v, pb[mt].v, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
         l_run[mt] = fmaf(l_run[mt], alpha[mt], ps[0]);
       }
+      if (FD > 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        Pack8 va;
-        va.v = *reinterpret_cast<const f16x8*>(&vs_[cur][k2][dt * 16 + l15][g4 * 8]);
+        if (FD == 0) vf[dt] = v_frag(dt);
+        else if (dt + FD < DT) vf[dt + FD] = v_frag(dt + FD);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          o[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.v, pb[mt].v, o[dt][mt], 0, 0, 0);
+          o[dt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pb[mt].v, o[dt][mt], 0, 0, 0);
+        if (FD > 0) __builtin_amdgcn_sched_barrier(0);
       }
     }
 
