@@ -9,8 +9,9 @@
  * forward pass over its KV cache, and the longest accepted path is selected
  * and appended (paper Sec. 4.1 "Task Formulation"; App. A.1 "Parallel
  * Verification"; Alg. 1, steps PackDraftsAsTree / Verification /
- * SelectLongestAcceptedPrefix / append).  Drafting itself (FSM, retrieval)
- * stays with the caller.
+ * SelectLongestAcceptedPrefix / append).  Drafting itself (FSM, retrieval) is
+ * not part of this header: toolspec_draft.h declares host-side drafting calls
+ * and the whole loop, built on the functions below.
  *
  * Conventions
  *  - All pointers are HOST pointers unless a parameter says "device".
