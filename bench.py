@@ -21,8 +21,11 @@ accepted draft tokens + bonus token, divided by the step time).  `roofline` is f
 dominant kernel (the fused gate/up projection): algorithmic weight bytes per launch over
 its mean duration between HIP events on the library's stream, measured in a second,
 event-bracketed repeat of the same steps right after the timed region (bracketing every
-launch inside the timed region itself would slow the step).  `cpu_baseline` is the CPU
-oracle, as it stands, on a bounded sample of the same workload.
+launch inside the timed region itself would slow the step).  `roofline.plain_read` is a
+reference point from the same run: a kernel that only reads, over the same weight tensors,
+between the same events; `step_frac_of_plain_read` relates the whole step's algorithmic
+bytes per second to it.  `cpu_baseline` is the CPU oracle, as it stands, on a bounded sample
+of the same workload.
 
 --workload w4 times the batched pass instead (16 paged requests, contexts U[2048, 16384], a
 32-node tree each: 528 rows through ts_verify_batch, then one commit per request).  Its
