@@ -24,8 +24,9 @@
 //   of two 16-key tiles pack straight into the B operand of
 //   O^T[dim][query] += V^T . P^T  A = V^T tile from LDS.  V pages are stored transposed in
 //                                 the cache ([head_dim][16 tokens]) exactly for this.
-// Soft-max is the running-max / rescale recurrence in fp32 on scores in log2 units, with the
-// reference rounded up to a whole number so that every rescale is an exact power of two;
+// Soft-max is the running-max / rescale recurrence in fp32 on scores in log2 units, with a
+// whole-number reference (the rounded-up maximum, followed lazily: see kRefSlack) so that every
+// rescale is an exact power of two;
 // probabilities 2^(s - ref) are rounded to half for the second product and the row sum
 // accumulates those rounded values (an extra MFMA against an all-ones operand, fp32 exact).
 // Partial (max, sum, O) per split are combined by k_attn_merge.
@@ -57,6 +58,13 @@ struct AttnArgs {
 __device__ __forceinline__ u32x4 to_half8(u32x4 v) {
   return u32x4{bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w)};
 }
+
+// The running soft-max reference of a row follows its maximum lazily: it moves only when the
+// rounded-up maximum exceeds it by more than this many powers of two.  Probabilities then reach
+// 2^kRefSlack at most (half holds 2^15), every rescale stays an exact power of two, and the O
+// rescale - 32 multiplies per row tile whenever any row of the wave moves its reference - runs a
+// few times per row instead of at most half blocks of a long context.
+constexpr float kRefSlack = 8.f;
 
 union Pack8 {
   f16x8 v;
@@ -285,7 +293,8 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
         // the running reference is a whole number (scores in log2 units): rescaling by exact
         // powers of two commutes with the bf16 rounding of the probabilities, so the result
         // does not depend on how keys are blocked or split
-        const float m_new = fmaxf(m_run[mt], ceilf(mx * a.scale));
+        const float m_ceil = ceilf(mx * a.scale);
+        const float m_new = (m_ceil > m_run[mt] + kRefSlack) ? m_ceil : m_run[mt];
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         alpha[mt] = __builtin_amdgcn_exp2f(m_run[mt] - m_use);
         rescale |= (m_new != m_run[mt]);
