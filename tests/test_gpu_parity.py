@@ -64,6 +64,29 @@ def test_verify_matches_oracle_random_trees(cfg_name, P, n_nodes):
         B.ts_kv_free(kv)
 
 
+@pytest.mark.parametrize("cfg_name,n_nodes", [("small_bf16", 64), ("small_bf16", 20), ("small_bf16_hd64", 40)])
+def test_softmax_reference_moving_late_in_the_context(cfg_name, n_nodes):
+    """The attention kernel moves a row's soft-max reference only when the running maximum exceeds
+    it by more than 2^8.  Random contexts settle the reference in the first key block; here the
+    keys grow along the context (x 1/4, 1/2, 1, 4, 16 by segment, exact in bf16), so the maximum
+    keeps climbing - by less than the slack inside a segment, by much more across segments - and
+    both the stale-reference path and the late rescale are compared with the oracle."""
+    cfg, w, model, omodel = U.get_model(cfg_name)
+    rng = np.random.default_rng(4242 + n_nodes)
+    P = 1100
+    K, V = wl.gen_context_kv(cfg, P, seed=91)
+    Kf = wl.bf16_bits_to_f32(K)
+    for seg, scale in enumerate((0.25, 0.5, 1.0, 4.0, 16.0)):
+        Kf[:, seg * 220:(seg + 1) * 220] *= scale
+    K = wl.f32_to_bf16_bits(Kf)
+    kv, okv = U.make_pair(cfg, model, K, V, int(rng.integers(cfg.vocab)))
+    try:
+        tok, par = _random_tree(rng, n_nodes, cfg.vocab)
+        U.check_verify(cfg, model, omodel, kv, okv, tok, par, label="%s growing keys n=%d" % (cfg_name, n_nodes))
+    finally:
+        B.ts_kv_free(kv)
+
+
 @pytest.mark.parametrize("cfg_name", ["small_fp32", "small_bf16"])
 def test_tree_shapes_of_the_workloads(cfg_name):
     """Chain, schema+alternatives+retrieved tree, BFS tree, retrieved continuations (32,16,8,8),
