@@ -141,6 +141,16 @@ ts_status ts_kv_set_page_table(ts_kv* kv, const int32_t* phys_page, int32_t n_pa
  * K already rotated.  Import sets the committed length to n_pos. */
 ts_status ts_kv_import(ts_kv* kv, int32_t n_pos, const void* k_host, const void* v_host);
 ts_status ts_kv_export(ts_kv* kv, int32_t pos0, int32_t n_pos, void* k_host, void* v_host);
+/* ts_kv_export for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the
+ * per-layer staging slabs that ts_kv_export allocates and frees on every call live in a 2 MiB
+ * device array that is part of the library image (every GPU the library runs on holds it until
+ * the process ends), so the call allocates and frees nothing.  One layer's K slab and V slab
+ * must each fit 1 MiB: n_pos * n_kv_heads * head_dim * element size <= 1048576 (512 positions of
+ * the 8B shape); larger requests fail with INVALID_ARG and copy nothing - export in pieces.  All
+ * calls on one GPU share the array, so calls that overlap in time on one GPU (two host threads,
+ * two models on the same device) race; calls in sequence do not. */
+ts_status ts_kv_export_noalloc(ts_kv* kv, int32_t pos0, int32_t n_pos, void* k_host, void* v_host);
 ts_status ts_set_pending(ts_kv* kv, int32_t token);   /* root token of the next verify */
 ts_status ts_kv_len(const ts_kv* kv, int32_t* committed_len);
 /* Roll the committed length back to new_len <= current length (drops later

@@ -21,7 +21,7 @@ TS_Q_OTHERS, TS_Q_TOOL_NAME, TS_Q_PARAM_NAME, TS_Q_PARAM_VALUE = 0, 1, 2, 3
 TS_DRAFT_NONE, TS_DRAFT_RETRIEVAL, TS_DRAFT_SCHEMA = 0, 1, 2
 
 EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits", "ts_get_hidden",
-           "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export",
+           "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export", "ts_kv_export_noalloc",
            "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_sample", "ts_verify_batch",
            "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read", "ts_profile_plain_read",
            "ts_drafter_create", "ts_drafter_free", "ts_drafter_retrieve", "ts_drafter_reset",
@@ -98,6 +98,7 @@ def load_library(path=None):
         "ts_kv_set_page_table": [C.c_void_p, i32p, C.c_int32],
         "ts_kv_import": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
         "ts_kv_export": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
+        "ts_kv_export_noalloc": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
         "ts_set_pending": [C.c_void_p, C.c_int32],
         "ts_kv_len": [C.c_void_p, i32p],
         "ts_kv_truncate": [C.c_void_p, C.c_int32],
@@ -227,6 +228,14 @@ def ts_kv_export(kv, pos0, n_pos, cfg):
     k = np.empty(shp, dtype=_np_dtype(cfg.dtype))
     v = np.empty(shp, dtype=_np_dtype(cfg.dtype))
     _check(load_library().ts_kv_export(kv, pos0, n_pos, k.ctypes.data, v.ctypes.data))
+    return k, v
+
+
+def ts_kv_export_noalloc(kv, pos0, n_pos, cfg):
+    shp = (cfg.n_layers, n_pos, cfg.n_kv_heads, cfg.head_dim)
+    k = np.empty(shp, dtype=_np_dtype(cfg.dtype))
+    v = np.empty(shp, dtype=_np_dtype(cfg.dtype))
+    _check(load_library().ts_kv_export_noalloc(kv, pos0, n_pos, k.ctypes.data, v.ctypes.data))
     return k, v
 
 

@@ -102,6 +102,28 @@ static hipError_t copy_sync(hipStream_t s, void* dst, const void* src, size_t by
   return hipStreamSynchronize(s);
 }
 
+// Static staging area of ts_kv_export_noalloc (the entry point for callers that cannot allocate).
+constexpr size_t kExportScratchBytes = (size_t)2 << 20;            // K slab in the first half, V slab in the second
+static __device__ __align__(256) unsigned char scratch[kExportScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];                            // device address of `scratch`, per device
+
+// Device address of this device's copy of `scratch` (each GPU holds its own copy at its own
+// address).  `device` must be the current device.  Host code never passes the array's name to a
+// kernel or a copy: on the host that name is only a handle for this lookup.
+static ts_status scratch_address(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return ts_fail(TS_ERR_INVALID_ARG, "device index %d outside [0,%d)", device, kMaxDevices);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return ts_fail(TS_ERR_DEVICE, "hipGetSymbolAddress(scratch) failed on device %d: %s", device, hipGetErrorString(e));
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return TS_OK;
+}
+
 static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 // ---------------------------------------------------------------------------------
@@ -371,6 +393,14 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
     return ts_fail(TS_ERR_DEVICE, "device setup failed: %s", hipGetErrorString(e));
   }
   m->n_cu = prop.multiProcessorCount;
+  {   // set-up: resolve this device's copy of the static staging area once, while the device is current
+    void* unused = nullptr;
+    if (scratch_address(m->device, &unused) != TS_OK) {
+      (void)hipStreamDestroy(m->stream);
+      delete m;
+      return TS_ERR_DEVICE;
+    }
+  }
   if (cfg->dtype == TS_DTYPE_BF16) {
     const GemmPlan p = gemm_bf16_plan(m, TS_MROWS_PER_BLOCK, cfg->vocab, cfg->d_model, 1);
     const int cols = gemm_bf16_cols_per_group(p.shape);
@@ -524,6 +554,36 @@ extern "C" ts_status ts_kv_export(ts_kv* kv, int32_t pos0, int32_t n_pos, void* 
   if (pos0 < 0 || n_pos < 0 || pos0 + n_pos > kv->capacity)
     return ts_fail(TS_ERR_INVALID_ARG, "positions [%d,%d) outside the capacity %d", pos0, pos0 + n_pos, kv->capacity);
   return kv_xfer_impl(kv, pos0, n_pos, nullptr, nullptr, k_host, v_host);
+}
+
+// ---------------------------------------------------------------------------------
+// export without allocation: the per-layer staging slabs live in a file-scope device array
+// ---------------------------------------------------------------------------------
+extern "C" ts_status ts_kv_export_noalloc(ts_kv* kv, int32_t pos0, int32_t n_pos, void* k_host, void* v_host) {
+  if (!kv || (n_pos > 0 && (!k_host || !v_host))) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  if (pos0 < 0 || n_pos < 0 || pos0 + n_pos > kv->capacity)
+    return ts_fail(TS_ERR_INVALID_ARG, "positions [%d,%d) outside the capacity %d", pos0, pos0 + n_pos, kv->capacity);
+  ts_model* m = kv->model;
+  const ts_model_config& c = m->cfg;
+  const size_t slab = (size_t)n_pos * c.n_kv_heads * c.head_dim * m->esz;   // one layer, K or V
+  if (slab > kExportScratchBytes / 2)
+    return ts_fail(TS_ERR_INVALID_ARG, "ts_kv_export_noalloc: %d positions need %zu bytes per layer slab, the static staging area holds %zu (at most %zu positions of this model per call)",
+                   n_pos, slab, kExportScratchBytes / 2, kExportScratchBytes / 2 / ((size_t)c.n_kv_heads * c.head_dim * m->esz));
+  if (n_pos == 0) return TS_OK;
+  (void)hipSetDevice(m->device);
+  void* base = nullptr;
+  ts_status st = scratch_address(m->device, &base);
+  if (st) return st;
+  void* sk = base;
+  void* sv = (char*)base + kExportScratchBytes / 2;
+  for (int l = 0; l < c.n_layers; ++l) {
+    launch_kv_export(kv, pos0, n_pos, sk, sv, l);
+    TS_HIP(hipGetLastError());
+    // both copies wait for completion, so the next layer may overwrite the slabs
+    TS_HIP(copy_sync(m->stream, (char*)k_host + (size_t)l * slab, sk, slab, hipMemcpyDeviceToHost));
+    TS_HIP(copy_sync(m->stream, (char*)v_host + (size_t)l * slab, sv, slab, hipMemcpyDeviceToHost));
+  }
+  return TS_OK;
 }
 
 extern "C" ts_status ts_set_pending(ts_kv* kv, int32_t token) {
