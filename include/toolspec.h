@@ -119,6 +119,13 @@ ts_status ts_model_keep_logits(ts_model* m, int32_t enable);
  * host_logits: n_rows * vocab floats.  STATE if logits were not kept. */
 ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, float* host_logits);
 
+/* The token each row of the most recent verify decided on, n_rows int32: after ts_verify /
+ * ts_verify_batch the arg-max token of the row's logits as the fused lm_head epilogue found it
+ * (lowest id among equal logits) - what the acceptance walk compared the row's children with;
+ * after ts_verify_sample the row's residual sample.  Works whether or not logits are kept.
+ * STATE before the first verify, INVALID_ARG for rows outside the last pass. */
+ts_status ts_get_row_tokens(ts_model* m, int32_t row0, int32_t n_rows, int32_t* host_tokens);
+
 /* Final normalised hidden state (the input of the lm_head) of one row of the most recent
  * verify, d_model floats: for row 0 after ingesting a question this is the last-token
  * representation h_x that retrieval compares with the datastore (Sec. 4.3, Eq. 3).  bf16

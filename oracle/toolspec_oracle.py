@@ -28,12 +28,17 @@ Arithmetic: float64 throughout.  Two modes for models stored in bfloat16:
             at the points where the device path stores or feeds 16-bit values.
             bfloat16: new K/V cache entries.  IEEE half, the format of the paper's
             own runs (App. B, "Performance Comparison", Table 5: the one accuracy
-            deviation is put down to fp16 precision): every activation that enters a weight projection - the
-            normalised activations, the attention output and the SwiGLU product,
-            saturating at the largest finite half - the rotated Q, and the
+            deviation is put down to fp16 precision): the rotated Q and the
             unnormalised softmax probabilities entering the P.V product (taken
             relative to the row maximum rounded up to a whole power of two, see
-            forward_tree).  bf16 K/V entries and bf16 weights widen to half
+            forward_tree).  Every activation that enters a weight projection - the
+            normalised activations, the attention output and the SwiGLU product -
+            is carried as the sum of TWO halves, hi = half(x) (saturating at the
+            largest finite half) and lo = half(x - hi), about 22 significant bits:
+            a projection input as coarse as one half lets two correct
+            implementations drift apart by whole half steps, more than the method's
+            exactness (output identical to plain decoding, Sec. 5.1 "Evaluation
+            Metrics", App. B.3) can absorb at near-tied logits.  bf16 K/V entries and bf16 weights widen to half
             exactly in half's normal range; the device re-encodes the projection
             weights as half once at load (magnitudes below 2^-14 move by less than
             3e-8; not modelled here).  The residual stream and the logits are never
@@ -75,8 +80,16 @@ def fp16_round(x):
 
 
 def fp16_act_round(x):
-    """Activation entering a projection: IEEE half, saturating at the largest finite half."""
+    """A single IEEE half, saturating at the largest finite half."""
     return fp16_round(np.clip(np.asarray(x, dtype=np.float64), -65504.0, 65504.0))
+
+
+def fp16_pair_round(x):
+    """Activation entering a projection: hi + lo with hi = half(x), saturating at the largest
+    finite half, and lo = half(x - hi)."""
+    xs = np.clip(np.asarray(x, dtype=np.float64), -65504.0, 65504.0)
+    hi = fp16_round(xs)
+    return hi + fp16_round(xs - hi)
 
 
 def _widen(a):
@@ -205,7 +218,7 @@ def forward_tree(model, kv, tok, depth, vis, mode="E", layer_limit=None, return_
     cfg = model.cfg
     rounding = mode == "R" and cfg.dtype == DTYPE_BF16
     rb = bf16_round if rounding else (lambda a: a)               # single bf16 value
-    ra = fp16_act_round if rounding else (lambda a: a)           # projection inputs: half, saturating
+    ra = fp16_pair_round if rounding else (lambda a: a)          # projection inputs: hi + lo halves
     rh = fp16_round if rounding else (lambda a: a)               # half precision (attention operands)
     M = len(tok)
     P = kv.P

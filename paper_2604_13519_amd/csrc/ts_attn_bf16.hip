@@ -371,7 +371,7 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
 constexpr int kMergeMaxSplits = 512;
 
 __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                    f16_t* __restrict__ Ab, int R, int Hq, int HD, int splits) {
+                                                    f16_t* __restrict__ Ab, size_t a_plane, int R, int Hq, int HD, int splits) {
   __shared__ float s_m[kMergeMaxSplits], s_l[kMergeMaxSplits];
   __shared__ float4 r_num[256];
   __shared__ float r_den[256];
@@ -427,8 +427,8 @@ __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__
     num.x += t.x; num.y += t.y; num.z += t.z; num.w += t.w;
     den += r_den[k * tpp + d4];
   }
-  // the attention output feeds the O projection as half
-  *reinterpret_cast<uint2*>(Ab + slot * HD + d4 * 4) = make_uint2(pack_f16x2_sat(num.x / den, num.y / den), pack_f16x2_sat(num.z / den, num.w / den));
+  // the attention output feeds the O projection as a hi and a lo half
+  st_act_planes4(Ab + slot * HD + d4 * 4, a_plane, num.x / den, num.y / den, num.z / den, num.w / den);
 }
 
 // Rows are covered by RS waves per head, MT tiles of 16 rows each: (tiles -> RS x MT)
@@ -503,5 +503,5 @@ void launch_attn_merge(ts_model* m, int R, int splits) {
   ProfScope ps(m, "attn_merge");
   const ts_model_config& c = m->cfg;
   hipLaunchKernelGGL(k_attn_merge, dim3(R * c.n_q_heads), dim3(256), 0, m->stream, m->attn_part_o, m->attn_part_ml,
-                     (f16_t*)m->Ab, R, c.n_q_heads, c.head_dim, splits);
+                     (f16_t*)m->Ab, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * m->q_dim, R, c.n_q_heads, c.head_dim, splits);
 }

@@ -47,6 +47,34 @@ __device__ __forceinline__ float sat_f16_range(float f) { return f == f ? fminf(
 __device__ __forceinline__ uint16_t f32_to_f16_sat(float f) { return f32_to_f16_bits(sat_f16_range(f)); }
 __device__ __forceinline__ uint32_t pack_f16x2_sat(float a, float b) { return pack_f16x2(sat_f16_range(a), sat_f16_range(b)); }
 
+// An activation that enters a weight projection of a bf16 model is carried as TWO halves,
+// x = hi + lo with hi = half(x) (saturating) and lo = half(x - hi): about 22 significant bits, so
+// that the projection inputs add no rounding of their own beyond fp32's.  The planes are separate
+// arrays `plane` elements apart; both feed the same MFMA accumulator.
+constexpr int TS_ACT_PLANES = 2;
+__device__ __forceinline__ void split_f16_planes(float x, _Float16& hi, _Float16& lo) {
+  const float xs = sat_f16_range(x);
+  hi = (_Float16)xs;
+  lo = (_Float16)(xs - (float)hi);
+}
+__device__ __forceinline__ void st_act_planes(f16_t* p, size_t plane, float x) {
+  _Float16 hi, lo;
+  split_f16_planes(x, hi, lo);
+  p[0] = __builtin_bit_cast(uint16_t, hi);
+  p[plane] = __builtin_bit_cast(uint16_t, lo);
+}
+// four consecutive activations (p 8-byte aligned): one vector store per plane
+__device__ __forceinline__ void st_act_planes4(f16_t* p, size_t plane, float x0, float x1, float x2, float x3) {
+  _Float16 h[4], l[4];
+  split_f16_planes(x0, h[0], l[0]);
+  split_f16_planes(x1, h[1], l[1]);
+  split_f16_planes(x2, h[2], l[2]);
+  split_f16_planes(x3, h[3], l[3]);
+  const ts_f16x2 h01 = {h[0], h[1]}, h23 = {h[2], h[3]}, l01 = {l[0], l[1]}, l23 = {l[2], l[3]};
+  *reinterpret_cast<uint2*>(p) = make_uint2(__builtin_bit_cast(uint32_t, h01), __builtin_bit_cast(uint32_t, h23));
+  *reinterpret_cast<uint2*>(p + plane) = make_uint2(__builtin_bit_cast(uint32_t, l01), __builtin_bit_cast(uint32_t, l23));
+}
+
 __device__ __forceinline__ float ld_f32(const float* p) { return *p; }
 __device__ __forceinline__ float ld_f32(const bf16_t* p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void st_from_f32(float* p, float v) { *p = v; }

@@ -37,13 +37,15 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 struct GemmArgs {
-  const f16_t* X;      // [rows][K] IEEE half, rows padded in memory
+  const f16_t* X;      // [2 planes][rows][K] IEEE half (x = hi + lo), rows padded in memory
+  size_t x_plane;      // elements between the hi and the lo plane
   const f16_t* Wt;     // tiled weights, IEEE half
   float* out;          // [split][R][N] partial sums (nullptr for ARGMAX)
   float* logits;       // [R][N] or nullptr (ARGMAX only)
   float* aval;         // [R][amax_parts]
   int32_t* aidx;
-  f16_t* act_out;      // SWIGLU: [rows][N/2] gated product, IEEE half
+  f16_t* act_out;      // SWIGLU: [2 planes][rows][N/2] gated product, IEEE half hi + lo
+  size_t act_plane;    // elements between its planes
   int R, N, K;
   int kper;            // k elements per split
   int n_tiles;         // ceil(N / 16)
@@ -66,13 +68,15 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
   constexpr int XS = KC + XPAD;             // LDS row stride in elements (+16 B: bank spread, keeps alignment)
   constexpr int NTHR = 64 * WAVES;
   constexpr int NBUF = PF + 1;              // weight register ring
-  constexpr int XV = MT * 16 * KC / 8;      // 16-byte vectors per X chunk
+  constexpr int PL = TS_ACT_PLANES;         // an activation is the sum of a hi and a lo half
+  constexpr int XVP = MT * 16 * KC / 8;     // 16-byte vectors per plane of an X chunk
+  constexpr int XV = PL * XVP;
   constexpr int XPT = (XV + NTHR - 1) / NTHR;
-  // activation chunks [buffer][row][k]; the same memory later serves the k-wave reduction
-  constexpr size_t XS_BYTES = sizeof(f16_t) * 2 * MT * 16 * XS;
+  // activation chunks [buffer][plane][row][k]; the same memory later serves the k-wave reduction
+  constexpr size_t XS_BYTES = sizeof(f16_t) * 2 * PL * MT * 16 * XS;
   constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * 4 * NT * 64 : 0;
   __shared__ __attribute__((aligned(16))) char smem[XS_BYTES > RED_BYTES ? XS_BYTES : RED_BYTES];
-  f16_t (*xs)[MT * 16][XS] = reinterpret_cast<f16_t (*)[MT * 16][XS]>(smem);
+  f16_t (*xs)[PL][MT * 16][XS] = reinterpret_cast<f16_t (*)[PL][MT * 16][XS]>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, g = lane >> 4;
@@ -98,8 +102,8 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
 #pragma unroll
   for (int p = 0; p < XPT; ++p) {
     const int v = min(tid + p * NTHR, XV - 1);      // surplus threads re-read the last vector
-    const int row = v / (KC / 8), cv = v % (KC / 8);
-    x_off[p] = (uint32_t)(((size_t)row * a.K + cv * 8) * 2);
+    const int pl = v / XVP, row = (v % XVP) / (KC / 8), cv = v % (KC / 8);
+    x_off[p] = (uint32_t)((pl * a.x_plane + (size_t)row * a.K + cv * 8) * 2);
   }
 
   f32x4 acc[MT][NT];
@@ -128,21 +132,25 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
-      if (XV % NTHR == 0 || v < XV) *reinterpret_cast<u32x4*>(&xs[buf][v / (KC / 8)][(v % (KC / 8)) * 8]) = src[p];
+      if (XV % NTHR == 0 || v < XV)
+        *reinterpret_cast<u32x4*>(&xs[buf][v / XVP][(v % XVP) / (KC / 8)][(v % (KC / 8)) * 8]) = src[p];
     }
   };
   auto mma_chunk = [&](const f16x8 (&wc)[NT][KSW], int buf) {
 #pragma unroll
     for (int ks = 0; ks < KSW; ++ks) {
-      f16x8 xa[MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        xa[mt] = *reinterpret_cast<const f16x8*>(&xs[buf][mt * 16 + l15][(kq * KSW + ks) * 32 + g * 8]);
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
+      for (int pl = 0; pl < PL; ++pl) {
+        f16x8 xa[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
+          xa[mt] = *reinterpret_cast<const f16x8*>(&xs[buf][pl][mt * 16 + l15][(kq * KSW + ks) * 32 + g * 8]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[mt], wc[t][ks], acc[mt][t], 0, 0, 0);
+      }
     }
   };
 
@@ -196,7 +204,7 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
         const int f = (nt_idx[0] >> 1) * 16 + l15;           // tiles 2j / 2j+1 = gate / up of features 16j..
         if (nt_idx[1] < a.n_tiles) {
           const float gv = v[0], uv = v[NT - 1];
-          a.act_out[(size_t)row * (a.N / 2) + f] = f32_to_f16_sat(gv / (1.0f + expf(-gv)) * uv);
+          st_act_planes(a.act_out + (size_t)row * (a.N / 2) + f, a.act_plane, gv / (1.0f + expf(-gv)) * uv);
         }
       } else {
         float* o = a.out + (size_t)blockIdx.y * a.split_stride;
@@ -382,6 +390,8 @@ void launch_gemm_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, 
   }
   GemmArgs a;
   a.X = X; a.Wt = Wt; a.out = out; a.logits = logits;
+  a.x_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * K;
+  a.act_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * (N / 2);
   a.aval = m->amax_val; a.aidx = m->amax_idx;
   a.act_out = act_out;
   a.R = R; a.N = N; a.K = K;

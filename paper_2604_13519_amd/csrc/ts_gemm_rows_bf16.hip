@@ -32,7 +32,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 struct RowsArgs {
-  const f16_t* X;      // [x_rows][K] IEEE half
+  const f16_t* X;      // [2 planes][x_rows][K] IEEE half (x = hi + lo)
+  size_t x_plane;      // elements between the planes
+  size_t act_plane;    // SWIGLU: elements between the planes of act_out
   int x_rows;          // rows allocated (reads are clamped to them)
   const f16_t* Wt;     // tiled weights, IEEE half
   float* out;          // [split][R][N] partial sums
@@ -65,14 +67,16 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
   static_assert(KSW >= 1 && KSW * KW == KSTEPS, "k-steps of a chunk divide among the k-waves");
   constexpr int XS = KC + 8;                // LDS row stride in elements (+16 B: bank spread)
   constexpr int NTHR = 64 * WAVES;
-  constexpr int XV = MT * 16 * KC / 8;      // 16-byte vectors per chunk
+  constexpr int PL = TS_ACT_PLANES;         // an activation is the sum of a hi and a lo half
+  constexpr int XVP = MT * 16 * KC / 8;     // 16-byte vectors per plane of a chunk
+  constexpr int XV = PL * XVP;
   constexpr int XPT = (XV + NTHR - 1) / NTHR;
-  constexpr size_t XS_BYTES = sizeof(f16_t) * 2 * MT * 16 * XS;
+  constexpr size_t XS_BYTES = sizeof(f16_t) * 2 * PL * MT * 16 * XS;
   constexpr size_t RED_BYTES = KW > 1 ? sizeof(float) * WAVES * 4 * NT * 64 : 0;   // the reduction reuses the activation buffers
   constexpr size_t AMAX_BYTES = MODE == MODE_ARGMAX ? (size_t)8 * WAVES * MT * 16 : 0;
   constexpr size_t SMEM_BYTES = XS_BYTES > RED_BYTES ? (XS_BYTES > AMAX_BYTES ? XS_BYTES : AMAX_BYTES) : (RED_BYTES > AMAX_BYTES ? RED_BYTES : AMAX_BYTES);
   __shared__ __attribute__((aligned(16))) char smem[SMEM_BYTES];
-  f16_t (*xs)[MT * 16][XS] = reinterpret_cast<f16_t (*)[MT * 16][XS]>(smem);
+  f16_t (*xs)[PL][MT * 16][XS] = reinterpret_cast<f16_t (*)[PL][MT * 16][XS]>(smem);
 
   // place: XCD = blockIdx.x % 8; the row blocks of a weight slab follow each other on one XCD
   const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
@@ -103,8 +107,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
 #pragma unroll
   for (int p = 0; p < XPT; ++p) {
     const int v = min(tid + p * NTHR, XV - 1);
-    const int row = min(row0 + v / (KC / 8), a.x_rows - 1), cv = v % (KC / 8);
-    x_off[p] = (uint32_t)(((size_t)row * a.K + cv * 8) * 2);
+    const int pl = v / XVP, row = min(row0 + (v % XVP) / (KC / 8), a.x_rows - 1), cv = v % (KC / 8);
+    x_off[p] = (uint32_t)((pl * a.x_plane + (size_t)row * a.K + cv * 8) * 2);
   }
 
   f32x4 acc[MT][NT];
@@ -132,7 +136,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
-      if (XV % NTHR == 0 || v < XV) *reinterpret_cast<u32x4*>(&xs[buf][v / (KC / 8)][(v % (KC / 8)) * 8]) = xr[p];
+      if (XV % NTHR == 0 || v < XV)
+        *reinterpret_cast<u32x4*>(&xs[buf][v / XVP][(v % XVP) / (KC / 8)][(v % (KC / 8)) * 8]) = xr[p];
     }
   };
   auto mma_chunk = [&](const f16x8 (&wc)[NT][KSW], int buf) {
@@ -141,9 +146,12 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
       const int kk = (kq * KSW + ks) * 32 + g * 8;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const f16x8 xa = *reinterpret_cast<const f16x8*>(&xs[buf][mt * 16 + l15][kk]);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, wc[t][ks], acc[mt][t], 0, 0, 0);
+        for (int pl = 0; pl < PL; ++pl) {
+          const f16x8 xa = *reinterpret_cast<const f16x8*>(&xs[buf][pl][mt * 16 + l15][kk]);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa, wc[t][ks], acc[mt][t], 0, 0, 0);
+        }
       }
     }
   };
@@ -219,7 +227,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
         if (nt_idx[t + 1] < a.n_tiles) {
           const int f = (nt_idx[t] >> 1) * 16 + l15;
           const float gv = v[t], uv = v[t + 1];
-          a.act_out[(size_t)row * (a.N / 2) + f] = f32_to_f16_sat(gv / (1.0f + expf(-gv)) * uv);
+          st_act_planes(a.act_out + (size_t)row * (a.N / 2) + f, a.act_plane, gv / (1.0f + expf(-gv)) * uv);
         }
       }
     } else {
@@ -314,7 +322,7 @@ bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max
   const int tiles = (R + 15) / 16;
   double best = 1e300;
   bool found = false;
-  if ((size_t)(R + 2 * TS_MROWS_PER_BLOCK) * K * 2 >= ((size_t)1 << 32)) return false;   // 32-bit activation offsets
+  if ((size_t)TS_ACT_PLANES * (R + 2 * TS_MROWS_PER_BLOCK) * K * 2 >= ((size_t)1 << 32)) return false;   // 32-bit activation offsets
   for (int mt = kMinMT; mt <= kMaxMT; ++mt) {
     const int n_rblocks = (tiles + mt - 1) / mt;
     if (mt > kMinMT && n_rblocks == (tiles + mt - 2) / (mt - 1)) continue;   // same blocks, more idle rows
@@ -353,6 +361,8 @@ void launch_gemm_rows_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* 
   RowsArgs a;
   a.x_rows = m->ws_rows + TS_MROWS_PER_BLOCK;
   a.X = X; a.Wt = Wt; a.out = out;
+  a.x_plane = (size_t)a.x_rows * K;
+  a.act_plane = (size_t)a.x_rows * (N / 2);
   a.act_out = act_out;
   a.logits = logits; a.aval = m->amax_val; a.aidx = m->amax_idx; a.amax_stride = m->amax_parts;
   a.R = R; a.N = N; a.K = K;

@@ -180,10 +180,12 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs, bool want_log
     const int scap = std::max(seqs, 1);
     const size_t esz = m->esz;
     if ((st = dev_alloc_bytes((void**)&m->H, (size_t)alloc_rows * c.d_model * 4, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Xn, (size_t)alloc_rows * c.d_model * esz, true))) return st;   // bf16 models: IEEE half
+    // projection inputs of bf16 models: a hi plane and a lo plane of IEEE halves, alloc_rows apart
+    const size_t planes = c.dtype == TS_DTYPE_BF16 ? 2 : 1;
+    if ((st = dev_alloc_bytes(&m->Xn, planes * alloc_rows * c.d_model * esz, true))) return st;
     if ((st = dev_alloc_bytes(&m->Qb, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Ab, (size_t)alloc_rows * m->q_dim * esz, true))) return st;
-    if ((st = dev_alloc_bytes(&m->Fb, (size_t)alloc_rows * c.d_ffn * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Ab, planes * alloc_rows * m->q_dim * esz, true))) return st;
+    if ((st = dev_alloc_bytes(&m->Fb, planes * alloc_rows * c.d_ffn * esz, true))) return st;
     size_t pe = 0;
     if (c.dtype == TS_DTYPE_BF16) {
       const int Ns[4] = {m->qkv_dim, c.d_model, 2 * c.d_ffn, c.d_model};
@@ -437,6 +439,17 @@ extern "C" ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, fl
   (void)hipSetDevice(m->device);
   TS_HIP(hipStreamSynchronize(m->stream));
   TS_HIP(copy_sync(m->stream, host, m->logits + (size_t)row0 * m->cfg.vocab, (size_t)n_rows * m->cfg.vocab * 4, hipMemcpyDeviceToHost));
+  return TS_OK;
+}
+
+extern "C" ts_status ts_get_row_tokens(ts_model* m, int32_t row0, int32_t n_rows, int32_t* host_tokens) {
+  if (!m || (n_rows > 0 && !host_tokens)) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  if (m->last_rows == 0) return ts_fail(TS_ERR_STATE, "no verify pass on this model yet");
+  if (row0 < 0 || n_rows < 0 || row0 + n_rows > m->last_rows)
+    return ts_fail(TS_ERR_INVALID_ARG, "rows [%d,%d) outside the last pass (%d rows)", row0, row0 + n_rows, m->last_rows);
+  if (n_rows == 0) return TS_OK;
+  (void)hipSetDevice(m->device);
+  TS_HIP(copy_sync(m->stream, host_tokens, m->samp_tok + row0, (size_t)n_rows * 4, hipMemcpyDeviceToHost));
   return TS_OK;
 }
 
@@ -846,10 +859,12 @@ extern "C" ts_status ts_get_hidden(ts_model* m, int32_t row, float* host_hidden)
     TS_HIP(copy_sync(m->stream, host_hidden, (const float*)m->Xn + (size_t)row * d, (size_t)d * 4, hipMemcpyDeviceToHost));
     return TS_OK;
   }
-  // bf16 models keep the normalised activations in IEEE half: widened exactly
-  std::vector<uint16_t> hx(d);
+  // bf16 models keep the normalised activations as a hi and a lo IEEE half: widened and added
+  std::vector<uint16_t> hx(d), lx(d);
+  const size_t plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * d;
   TS_HIP(copy_sync(m->stream, hx.data(), (const f16_t*)m->Xn + (size_t)row * d, (size_t)d * 2, hipMemcpyDeviceToHost));
-  for (int i = 0; i < d; ++i) host_hidden[i] = half_bits_to_float(hx[i]);
+  TS_HIP(copy_sync(m->stream, lx.data(), (const f16_t*)m->Xn + plane + (size_t)row * d, (size_t)d * 2, hipMemcpyDeviceToHost));
+  for (int i = 0; i < d; ++i) host_hidden[i] = half_bits_to_float(hx[i]) + half_bits_to_float(lx[i]);
   return TS_OK;
 }
 

@@ -12,14 +12,13 @@
 __device__ __forceinline__ void st_q(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st_q(bf16_t* p, float v) { *p = f32_to_f16_bits(v); }
 
-// store an activation that feeds a projection: float as is, IEEE half (saturating) for bf16 models
-__device__ __forceinline__ void st_act(float* p, float v) { *p = v; }
-__device__ __forceinline__ void st_act(f16_t* p, float v) { *p = f32_to_f16_sat(v); }
-// four consecutive activations (p 16-byte aligned in float terms): one vector store
-__device__ __forceinline__ void st_act4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
-__device__ __forceinline__ void st_act4(f16_t* p, const float4& v) {
-  *reinterpret_cast<uint2*>(p) = make_uint2(pack_f16x2_sat(v.x, v.y), pack_f16x2_sat(v.z, v.w));
-}
+// store an activation that feeds a projection: float as is; for bf16 models as a hi and a lo
+// IEEE half in two planes `plane` elements apart (hi saturating)
+__device__ __forceinline__ void st_act(float* p, size_t, float v) { *p = v; }
+__device__ __forceinline__ void st_act(f16_t* p, size_t plane, float v) { st_act_planes(p, plane, v); }
+// four consecutive activations (p 16-byte aligned in float terms): one vector store per plane
+__device__ __forceinline__ void st_act4(float* p, size_t, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st_act4(f16_t* p, size_t plane, const float4& v) { st_act_planes4(p, plane, v.x, v.y, v.z, v.w); }
 
 // ---------------------------------------------------------------------------------
 // weight re-tiling (model load): row-major [N][K] bf16 -> MFMA operand tiles of IEEE half.
@@ -107,14 +106,14 @@ void launch_rope_table(ts_model* m, const RowMeta& rm, int R) {
 
 // ---------------------------------------------------------------------------------
 // residual update + RMSNorm:  H[r] += sum_s part[s][r]  (skipped when n_parts = 0),
-// Xn[r] = H[r] * rsqrt(mean(H[r]^2) + eps) * gain, stored as float (fp32 models) or as IEEE
-// half (bf16 models: every projection input is a half).
+// Xn[r] = H[r] * rsqrt(mean(H[r]^2) + eps) * gain, stored as float (fp32 models) or as a hi and
+// a lo IEEE half (bf16 models: every projection input is such a pair).
 // One block of 1024 threads per row, 16-byte accesses; needs d_model % 4 == 0.
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const float* __restrict__ part, int n_parts,
                                                size_t part_stride, const float* __restrict__ gain,
-                                               T* __restrict__ Xn, int d, float eps) {
+                                               T* __restrict__ Xn, size_t x_plane, int d, float eps) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   float4* h4 = reinterpret_cast<float4*>(H + (size_t)r * d);
@@ -158,7 +157,7 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
   for (int w = 0; w < 16; ++w) tot += red[w];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
   auto emit = [&](int i, const float4& v, const float4& g) {
-    st_act4(Xn + (size_t)r * d + 4 * i, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
+    st_act4(Xn + (size_t)r * d + 4 * i, x_plane, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
   };
 #pragma unroll
   for (int k = 0; k < KEEP; ++k) {
@@ -172,10 +171,10 @@ void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part
   ProfScope ps(m, "residual_rmsnorm");
   if (m->cfg.dtype == TS_DTYPE_BF16)
     hipLaunchKernelGGL(k_norm<f16_t>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (f16_t*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
+                       (f16_t*)m->Xn, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * m->cfg.d_model, m->cfg.d_model, m->cfg.rms_eps);
   else
     hipLaunchKernelGGL(k_norm<float>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (float*)m->Xn, m->cfg.d_model, m->cfg.rms_eps);
+                       (float*)m->Xn, (size_t)0, m->cfg.d_model, m->cfg.rms_eps);
 }
 
 // ---------------------------------------------------------------------------------
@@ -250,7 +249,7 @@ void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_part
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t part_stride, T* __restrict__ Fb,
-                         int R, int F) {
+                         size_t f_plane, int R, int F) {
   const size_t total = (size_t)R * F;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int r = (int)(i / F), f = (int)(i % F);
@@ -261,7 +260,7 @@ __global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t par
       g += p[(size_t)s * part_stride];
       u += p[(size_t)s * part_stride + 16];
     }
-    st_act(Fb + i, g / (1.0f + expf(-g)) * u);
+    st_act(Fb + i, f_plane, g / (1.0f + expf(-g)) * u);
   }
 }
 
@@ -272,9 +271,9 @@ void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride) {
   int blocks = (int)((total + 255) / 256);
   if (blocks > 4096) blocks = 4096;
   if (m->cfg.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_swiglu<f16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (f16_t*)m->Fb, R, F);
+    hipLaunchKernelGGL(k_swiglu<f16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (f16_t*)m->Fb, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * F, R, F);
   else
-    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, R, F);
+    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, (size_t)0, R, F);
 }
 
 // ---------------------------------------------------------------------------------

@@ -1,12 +1,13 @@
 """Shared helpers of the GPU parity tests: build the same model / cache / tree on the
 HIP library and in the CPU oracle, and compare them under the stated rules.
 
-Rules (floating point): logits relative L2 <= 1e-5 on the fp32 path; on the bf16 path
-<= 2e-2 against the oracle's exact mode "E" and <= 1e-2 against its rounding-emulating
-mode "R" (same bf16 rounding points, float64 accumulation).  Against mode "R" most rows
-agree to ~1e-7; what remains are sparse one-ulp bf16 flips (a value within 1e-7 of a
-rounding boundary lands on the other side in fp32), each worth up to a few 1e-3 on the
-row it hits in the narrowest test models.  Integers (accept length, tokens,
+Rules (floating point).  The CONTRACT: logits relative L2 <= 1e-5 on the fp32 path and
+<= 2e-2 on the bf16 path, both against the oracle's exact float64 mode "E".  A CANARY on top of
+it, self-imposed: <= 3e-3 against the rounding-emulating mode "R" (same 16-bit rounding points,
+float64 accumulation) - most rows agree to ~1e-6 there; what remains are sparse one-step flips
+of a 16-bit value (a new bf16 K/V entry, a half Q entry or probability within 1e-7 of a
+rounding boundary lands on the other side in fp32).  It is tighter than the contract so that a
+misplaced rounding on the device shows long before the contract breaks.  Integers (accept length, tokens,
 node ids, bonus, cache layout) are bit-exact against mode "R" (fp32: mode "E"), except
 that a row whose oracle top-2 logit margin is below 1e-2 may pick the runner-up; every
 arg-max disagreement must be such a row and the walk must be exact given the arg-maxes.
@@ -19,19 +20,10 @@ from paper_2604_13519_amd import binding as B
 
 MARGIN = 1e-2
 TOL_F32 = 1e-5
-TOL_BF16_E = 2e-2
-TOL_BF16_R = 1e-2
+TOL_BF16_E = 2e-2      # the contract (vs mode E)
+TOL_BF16_R = 3e-3      # canary (vs mode R)
 
 _models = {}
-
-
-def _stat(line):
-    """Measured errors are appended to gpurun_out/parity_stats.txt when that folder exists."""
-    import os
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "parity_stats.txt"), "a") as f:
-            f.write(line + "\n")
 
 
 def rel_l2(a, b):
@@ -94,18 +86,19 @@ def check_verify(cfg, model, omodel, kv, okv, tok, par, check_kv=True, label="")
     oR = O.verify(omodel, okv, tok, par, "E" if fp32 else "R")
     tolE, tolR = tolerances(cfg)
     errR = max(rel_l2(glog[r], oR.logits[r]) for r in range(M))
-    _stat("%s: M=%d P=%d logits vs decision-mode oracle %.3g (min decisive margin %.3g)" % (label, M, P, errR, oR.decisive_margin))
+    print("%s: M=%d P=%d logits vs decision-mode oracle %.3g (min decisive margin %.3g)" % (label, M, P, errR, oR.decisive_margin))
     errE = None
     if not fp32:
         oE = O.verify(omodel, okv, tok, par, "E")
         errE = max(rel_l2(glog[r], oE.logits[r]) for r in range(M))
-        _stat("%s: logits vs exact oracle %.3g; mode R vs mode E %.3g" % (
+        print("%s: logits vs exact oracle %.3g; mode R vs mode E %.3g" % (
             label, errE, max(rel_l2(oR.logits[r], oE.logits[r]) for r in range(M))))
     assert errR <= tolR, "%s logits vs decision-mode oracle: rel L2 %.3g > %.3g" % (label, errR, tolR)
     if errE is not None:
         assert errE <= tolE, "%s logits vs exact oracle: rel L2 %.3g > %.3g" % (label, errE, tolE)
-    # integer decisions
+    # integer decisions: the tokens the fused lm_head epilogue decided on are the arg-max of the logits
     g_gpu = np.argmax(glog, axis=1)
+    assert np.array_equal(B.ts_get_row_tokens(model, 0, M), g_gpu), "%s fused arg-max != arg-max of the stored logits" % label
     tokr, parr, depth, _ = oR.rows
     for r in np.nonzero(g_gpu != oR.greedy)[0]:
         assert oR.margin[r] < MARGIN, "%s row %d arg-max differs with oracle margin %.4g" % (label, r, oR.margin[r])
@@ -120,7 +113,7 @@ def check_verify(cfg, model, omodel, kv, okv, tok, par, check_kv=True, label="")
         gk, gv = B.ts_kv_export(kv, P, M, cfg)
         if not fp32:
             gk, gv = wl.bf16_bits_to_f32(gk), wl.bf16_bits_to_f32(gv)
-        tol = 1e-5 if fp32 else 1e-2      # bf16 entries: one-ulp flips of single elements allowed
+        tol = 1e-5 if fp32 else 3e-3      # bf16 entries: one-step flips of single elements allowed (canary, as above)
         assert rel_l2(gk, oR.newK) <= tol, "%s tree K rows: %.3g" % (label, rel_l2(gk, oR.newK))
         assert rel_l2(gv, oR.newV) <= tol, "%s tree V rows: %.3g" % (label, rel_l2(gv, oR.newV))
     return res, oR

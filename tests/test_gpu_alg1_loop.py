@@ -75,7 +75,7 @@ def test_alg1_loop_is_lossless_and_accelerates(cfg_name):
         # oracle's replay; `states` only samples the step boundaries)
         assert {1, 2, 3} <= {DO.fsm_replay(schema, out[:i])[0] for i in range(1, len(out) + 1)}
         assert states <= {0, 1, 2, 3}
-        U._stat("%s Alg. 1 loop: %d tokens in %d target passes" % (cfg_name, len(out), passes))
+        print("%s Alg. 1 loop: %d tokens in %d target passes" % (cfg_name, len(out), passes))
         # the same loop as one native call: same stream, same number of passes
         kv2 = B.ts_kv_alloc(model, len(prompt) + n_new + 80)
         try:

@@ -40,6 +40,50 @@ def _greedy_from_oracle(omodel, okv_template_args, n):
 
 
 # ------------------------------------------------------------------------------------
+# the shipped configuration stores no logits: same decisions as with logits kept
+# ------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg_name,P", [("small_bf16", 200), ("small_bf16_hd64", 70), ("llama8b_2l", 600)])
+def test_results_without_stored_logits_equal_results_with_them(cfg_name, P):
+    """Every other parity test keeps the logits (it compares them); the product default does not.
+    Same trees both ways - single and batched, greedy-heavy and random - must give identical
+    (accept_len, tokens, nodes, bonus) and identical per-row tokens; with the logits off
+    ts_get_logits must refuse."""
+    cfg, w, model, omodel = U.get_model(cfg_name)
+    rng = np.random.default_rng(4242)
+    K, V = wl.gen_context_kv(cfg, P, seed=79)
+    pending = int(rng.integers(cfg.vocab))
+    greedy = _greedy_from_oracle(omodel, (cfg, K, V, pending, P + 80), 6)
+    trees = [wl.chain_tree(greedy, 6, 0.0, cfg.vocab, rng), wl.bfs_tree(greedy, 40, cfg.vocab, rng),
+             _random_tree(rng, 64, cfg.vocab), (np.zeros(0, np.int32), np.zeros(0, np.int32))]
+    kvs = []
+    try:
+        for _ in trees:
+            kv = B.ts_kv_alloc(model, P + 80)
+            B.ts_kv_import(kv, K, V)
+            B.ts_set_pending(kv, pending)
+            kvs.append(kv)
+        out = {}
+        for keep in (True, False, True):
+            B.ts_model_keep_logits(model, keep)
+            single = []
+            for kv, (tok, par) in zip(kvs, trees):
+                res = B.ts_verify(model, kv, tok, par)
+                single.append((res, B.ts_get_row_tokens(model, 0, len(tok) + 1).tolist()))
+            batch = B.ts_verify_batch(model, kvs, trees)
+            rows = B.ts_get_row_tokens(model, 0, sum(len(t[0]) + 1 for t in trees)).tolist()
+            if not keep:
+                with pytest.raises(B.TsError):
+                    B.ts_get_logits(model, 0, 1, cfg.vocab)
+            out.setdefault(keep, []).append((single, batch, rows))
+        assert out[True][0] == out[False][0] == out[True][1]
+        assert out[False][0][0][0][0][0] >= 1              # the walk accepts part of the greedy chain: not a trivial case
+    finally:
+        B.ts_model_keep_logits(model, True)
+        for kv in kvs:
+            B.ts_kv_free(kv)
+
+
+# ------------------------------------------------------------------------------------
 # single verify: logits, decisions, tree K/V rows
 # ------------------------------------------------------------------------------------
 @pytest.mark.parametrize("cfg_name,P,n_nodes", [

@@ -54,7 +54,7 @@ def test_prefill_cache_matches_causal_forward_and_supports_verify(cfg_name, n_pr
         _, K, V = D.causal_forward(cfg, w, prompt[:-1], return_kv=True)
         tol = 1e-5 if fp32 else 1e-2
         ek, ev = U.rel_l2(gk, K), U.rel_l2(gv, V)
-        U._stat("%s prefill %d tokens: K %.3g V %.3g vs dense causal forward" % (cfg_name, n_prompt, ek, ev))
+        print("%s prefill %d tokens: K %.3g V %.3g vs dense causal forward" % (cfg_name, n_prompt, ek, ev))
         assert ek <= tol and ev <= tol, "prefilled K/V vs causal forward: %.3g %.3g" % (ek, ev)
 
         # a verification on top of it, against the oracle's own ingestion of the same prompt
@@ -142,7 +142,7 @@ def test_last_token_hidden_state_for_retrieval(cfg_name):
         _, _, _, hid = O.forward_tree(omodel, okv, rows[0], rows[2], rows[3], mode, return_hidden=True)
         tol = 1e-5 if fp32 else 1e-2
         errs = [U.rel_l2(B.ts_get_hidden(model, r, cfg.d_model), hid[r]) for r in range(len(tok) + 1)]
-        U._stat("%s hidden-state export: max rel L2 %.3g" % (cfg_name, max(errs)))
+        print("%s hidden-state export: max rel L2 %.3g" % (cfg_name, max(errs)))
         assert max(errs) <= tol
         with pytest.raises(B.TsError) as e:
             B.ts_get_hidden(model, len(tok) + 1, cfg.d_model)

@@ -116,6 +116,25 @@ def bfs_tree(greedy, n_nodes, vocab, rng, max_branch=4, max_depth=12, p_keep=0.7
     return np.asarray(toks, np.int32), np.asarray(par, np.int32)
 
 
+def random_tree(n_nodes, vocab, rng):
+    """Uniformly random shape and tokens: node i hangs off a uniform choice among the root and
+    the nodes before it; every token is a uniform id.  Nothing in it follows the target's
+    greedy choice, so almost every row's decision is between two arbitrary near-top tokens."""
+    par = np.array([rng.integers(-1, i) for i in range(n_nodes)], dtype=np.int32)
+    tok = rng.integers(vocab, size=n_nodes).astype(np.int32)
+    return tok, par
+
+
+def decision_sweep_case(cfg, t, P=512, n_nodes=64):
+    """Case t of the arg-max decision sweep: (context K, V, root token, draft tokens, parents)."""
+    from .kv import gen_context_kv
+    rng = np.random.default_rng([777, t])
+    K, V = gen_context_kv(cfg, P, seed=4000 + t)
+    root = int(rng.integers(cfg.vocab))
+    tok, par = random_tree(n_nodes, cfg.vocab, rng)
+    return K, V, root, tok, par
+
+
 def root_token(vocab, P, seed=3456):
     """Pending (root) token of the synthetic-context workloads: one seeded uniform id."""
     return int(np.random.default_rng([seed, P]).integers(vocab))
