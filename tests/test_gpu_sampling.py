@@ -65,7 +65,7 @@ def test_sampled_walk_matches_the_oracle(cfg_name):
                         B.ts_kv_commit(kv)          # the result is committable like a greedy one
                         B.ts_kv_truncate(kv, 150)
                         B.ts_set_pending(kv, 11)
-        U._stat("%s sampling: %d of %d cases compared exactly" % (cfg_name, exact, total))
+        print("%s sampling: %d of %d cases compared exactly" % (cfg_name, exact, total))
         assert exact >= 0.6 * total
     finally:
         B.ts_kv_free(kv)
@@ -95,7 +95,7 @@ def test_first_token_distribution_on_the_device():
             counts[j[0] if len(j) else 6] += 1
         expect = np.concatenate([p[top], [1.0 - p[top].sum()]]) * n
         chi2 = np.sum((counts - expect) ** 2 / expect)
-        U._stat("sampling first-token chi2 %.2f (df 6), p(top) %s" % (chi2, np.round(p[top], 4)))
+        print("sampling first-token chi2 %.2f (df 6), p(top) %s" % (chi2, np.round(p[top], 4)))
         assert chi2 < stats.chi2.ppf(0.999, df=6), (chi2, counts, expect)
     finally:
         B.ts_kv_free(kv)
