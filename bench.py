@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the tree-verify step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload w3|w2|w4|w5|dev]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload w3|w2|w6|w4|w5|e2e|dev]
 
 A step is one pass of the whole hot path over one draft tree: ts_verify (tree ingest,
 32-layer masked forward pass, fused vocab arg-max, acceptance walk, result to host) followed
@@ -17,15 +17,28 @@ argument chain, four 8-token retrieved branches), mutated greedy continuation.
 runs in IEEE half with fp32 accumulation (bf16 values widen to half exactly).
 
 Prints ONE JSON line.  `value` = accepted tokens per second (tokens emitted per step =
-accepted draft tokens + bonus token, divided by the step time).  `roofline` is for the
+accepted draft tokens + bonus token, divided by the step time).  `verify_ms` is the median of at
+least 50 ts_verify passes, each timed between two HIP events on the library's stream (first
+launch .. acceptance walk); `verify_wall_ms` is the host's clock around the same calls.
+`roofline` is for the
 dominant kernel (the fused gate/up projection): algorithmic weight bytes per launch over
 its mean duration between HIP events on the library's stream, measured in a second,
 event-bracketed repeat of the same steps right after the timed region (bracketing every
 launch inside the timed region itself would slow the step).  `roofline.plain_read` is a
 reference point from the same run: a kernel that only reads, over the same weight tensors,
 between the same events; `step_frac_of_plain_read` relates the whole step's algorithmic
-bytes per second to it.  `cpu_baseline` is the CPU oracle, as it stands, on a bounded sample
-of the same workload.
+bytes per second to it.  `roofline.traffic` is read from profiles/traffic.json (two rocprofv3
+counter passes, turned into that file by `python -m paper_2604_13519_amd.counters`; the file
+names the commit it was measured on, reported as `traffic_commit`).  `cpu_baseline` is the CPU
+oracle, as it stands, timed on ONE whole verify step of the same workload (all layers, lm_head,
+acceptance walk).
+
+--workload w6: the retrieval shape of the paper (continuations of 32, 16, 8 and 8 tokens from the
+root, App. B.2) on the same model and context.  --workload e2e: the whole loop on the 8B shape -
+a real ts_prefill of an 8192-token random prompt, then ts_generate (host drafter: schema FSM +
+suffix match over retrieved calls, Alg. 1) next to plain decoding of the same tokens; it reports
+prefill tokens/s, decoding tokens/s with and without drafts, and the host drafting share of the
+decoding time (the paper's time-allocation figure puts 5.7 % of its runtime there, Sec. 5.3).
 
 --workload w4 times the batched pass instead (16 paged requests, contexts U[2048, 16384], a
 32-node tree each: 528 rows through ts_verify_batch, then one commit per request).  Its
@@ -54,7 +67,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="w3", choices=["w3", "w2", "w4", "w5", "dev"])
+    ap.add_argument("--workload", default="w3", choices=["w3", "w2", "w6", "w4", "w5", "e2e", "dev"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -65,6 +78,8 @@ def workload(name):
         return "llama8b", 8192, "schema", "llama3-8b-shape bf16, batch 1, ctx 8192, 64-node schema+alternatives+retrieved tree"
     if name == "w2":
         return "llama8b", 4096, "chain16", "llama3-8b-shape bf16, batch 1, ctx 4096, chain of 16 (p=0.2)"
+    if name == "w6":
+        return "llama8b", 8192, "retrieval", "llama3-8b-shape bf16, batch 1, ctx 8192, retrieved continuations of 32/16/8/8 tokens"
     return "llama8b_2l", 4096, "schema", "DEV ONLY: 2 layers of the 8b layer shape, ctx 4096, 64-node tree"
 
 
@@ -74,6 +89,8 @@ def build_trees(wl, cfg, kind, greedy, n_trees=32):
         rng = np.random.default_rng([3456, s])
         if kind == "schema":
             trees.append(wl.schema_retrieval_tree(greedy, cfg.vocab, rng))
+        elif kind == "retrieval":
+            trees.append(wl.retrieval_tree(greedy, cfg.vocab, rng))
         else:
             trees.append(wl.chain_tree(greedy, 16, 0.2, cfg.vocab, rng))
     return trees
@@ -84,34 +101,26 @@ def algorithmic_bytes(cfg, P):
 
 
 def cpu_baseline(wl, cfg, weights, K, V, root, tree, mean_tokens):
-    """Oracle forward pass of the same tree on a bounded sample: the first 2 and the first 4
-    layers (plus final norm and lm_head each time); per-layer and head times are separated by
-    differencing and scaled to all layers."""
+    """One whole verify step of the oracle as it stands (float64, mode R): every layer, the
+    lm_head, the arg-max and the acceptance walk, on the first tree of the workload."""
     from oracle import toolspec_oracle as O
     om = O.OracleModel(cfg, weights)
     okv = O.OracleKV(cfg, K.shape[1] + len(tree[0]) + 1)
-    okv.K[:4, :K.shape[1]] = O._widen(K[:4])
-    okv.V[:4, :K.shape[1]] = O._widen(V[:4])
-    okv.P = K.shape[1]
-    rows = O.tree_rows(root, tree[0], tree[1])
-    t = {}
-    for nl in (2, 4):
-        t0 = time.time()
-        O.forward_tree(om, okv, rows[0], rows[2], rows[3], mode="R", layer_limit=min(nl, cfg.n_layers))
-        t[nl] = time.time() - t0
-    per_layer = max((t[4] - t[2]) / 2.0, 1e-9)
-    head = max(t[2] - 2 * per_layer, 0.0)
-    full = head + cfg.n_layers * per_layer
+    okv.import_context(K, V)
+    okv.pending = int(root)
+    t0 = time.time()
+    r = O.verify(om, okv, tree[0], tree[1], "R")
+    full = time.time() - t0
     try:
         import threadpoolctl
         cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": mean_tokens / full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": "oracle forward_tree (mode R, float64) of one %d-row tree timed on layers 0-1 (%.1f s) and "
-                      "0-3 (%.1f s) incl. lm_head; per-layer %.2f s and head %.2f s scaled to %d layers = %.1f s per "
-                      "verify step" % (len(rows[0]), t[2], t[4], per_layer, head, cfg.n_layers, full),
-            "est_step_s": full}
+            "sample": "one whole oracle verify step (mode R, float64, all %d layers + lm_head + walk) of the first %d-row "
+                      "tree of the workload: %.1f s, accept_len %d; tokens/s = the workload's mean tokens per step / that time"
+                      % (cfg.n_layers, len(tree[0]) + 1, full, r.accept_len),
+            "step_s": full}
 
 
 def main_batched(a, wl, B, torch):
@@ -194,6 +203,76 @@ def main_batched(a, wl, B, torch):
     print(json.dumps(out))
 
 
+def main_e2e(a, wl, B, torch):
+    """The whole loop (Alg. 1) on the 8B shape: real ingestion of an 8192-token prompt, then decoding
+    of N tokens twice - plain (one token per target pass) and with the host drafter - from the same
+    cache state.  The target's own plain stream serves as the recurring historical call the
+    retrieval drafter finds (the repeated-call case of Sec. 5.3) and as the text the schema follows."""
+    cfg = wl.get_config("llama8b")
+    P, n_new = 8192, 128
+    model = B.ts_model_load(cfg, wl.gen_weights(cfg, 1234))
+    rng = np.random.default_rng([2024, 8])
+    prompt = rng.integers(cfg.vocab, size=P).astype(np.int32)
+    kv = B.ts_kv_alloc(model, P + n_new + 160)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    B.ts_prefill(model, kv, prompt)
+    prefill_s = time.perf_counter() - t0
+    print("[bench] prompt of %d tokens ingested in %.2f s" % (P, prefill_s), file=sys.stderr, flush=True)
+    # plain decoding = the same loop with a drafter that never has anything to propose
+    r3 = lambda: [int(t) for t in rng.integers(cfg.vocab, size=3)]
+    empty = B.ts_drafter_create({"call_open": r3(), "name_prefix": r3(), "name_suffix": r3(), "param_prefix": r3(),
+                                 "param_suffix": r3(), "value_end": r3(), "call_close": r3(), "tools": [r3()], "params": [[r3()]]})
+    t0 = time.perf_counter()
+    g, st_plain = B.ts_generate(model, kv, empty, n_new)
+    plain_s = time.perf_counter() - t0
+    B.ts_drafter_free(empty)
+    rnd = lambda n: [int(t) for t in rng.integers(cfg.vocab, size=n)]
+    schema = {"call_open": g[2:3], "name_prefix": g[3:5], "name_suffix": g[7:9], "param_prefix": g[9:10],
+              "param_suffix": g[11:12], "value_end": g[15:16], "call_close": rnd(2),
+              "tools": [rnd(2), g[5:7], rnd(3)] + [rnd(3) for _ in range(5)], "params": [[rnd(1)], [rnd(2), g[10:11]], []] + [[] for _ in range(5)]}
+    calls = [rnd(200) for _ in range(9)]
+    calls.insert(1, list(g[18:]))
+    H = rng.standard_normal((len(calls), cfg.d_model)).astype(np.float32)
+    h_x = H[1] + 0.01 * rng.standard_normal(cfg.d_model).astype(np.float32)
+    d = B.ts_drafter_create(schema)
+    B.ts_drafter_retrieve(d, h_x, H, calls, k=10)
+    runs = []
+    for _ in range(max(1, a.steps // 8)):
+        B.ts_kv_truncate(kv, P - 1)
+        B.ts_set_pending(kv, int(prompt[-1]))
+        B.ts_drafter_reset(d)
+        t0 = time.perf_counter()
+        out, st = B.ts_generate(model, kv, d, n_new)
+        runs.append((time.perf_counter() - t0, out, st))
+    spec_s, out, st = sorted(runs, key=lambda r: r[0])[len(runs) // 2]
+    same = 0
+    while same < min(len(out), len(g)) and out[same] == g[same]:
+        same += 1
+    res = {
+        "metric": "end-to-end tokens/s of the decoding loop (ingestion + drafting + verification + commit), 8B bf16",
+        "value": len(out) / spec_s, "unit": "tokens/s", "n_gpus": 1, "steps": st["steps"], "warmup": 0,
+        "ms_per_step": spec_s / max(st["steps"], 1) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "llama3-8b-shape bf16, batch 1: real ingestion of an 8192-token random prompt, then %d tokens "
+                               "decoded by the whole loop (schema FSM + retrieval drafts, trees of <= 64 nodes)" % n_new,
+                   "context": P, "new_tokens": len(out)},
+        "prefill_tokens_per_s": P / prefill_s, "prefill_s": prefill_s,
+        "decode_tokens_per_s": len(out) / spec_s, "plain_decode_tokens_per_s": len(g) / plain_s,
+        "speedup_vs_plain_decoding": (len(out) / spec_s) / (len(g) / plain_s),
+        "end_to_end_tokens_per_s": len(out) / (prefill_s + spec_s),
+        "target_passes": st["steps"], "mean_tokens_per_pass": len(out) / max(st["steps"], 1),
+        "retrieval_steps": st["retrieval_steps"], "schema_steps": st["schema_steps"], "plain_steps": st["plain_steps"],
+        "drafting_share_of_decoding": st["draft_seconds"] / max(st["draft_seconds"] + st["verify_seconds"], 1e-12),
+        "paper_drafting_share": 0.057,
+        "stream_equals_plain_decoding_for": same, "plain_tokens": len(g),
+    }
+    B.ts_drafter_free(d)
+    B.ts_kv_free(kv)
+    B.ts_model_free(model)
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -211,6 +290,8 @@ def main():
 
     if a.workload in ("w4", "w5"):
         return main_batched(a, wl, B, torch)
+    if a.workload == "e2e":
+        return main_e2e(a, wl, B, torch)
     cfg_name, P, tree_kind, desc = workload(a.workload)
     cfg = wl.get_config(cfg_name)
     t0 = time.time()
@@ -256,12 +337,21 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
 
-    # verify-only latency (no commit), same trees
+    # verify-only latency (no commit), same trees: every pass between two HIP events on the
+    # library's stream, median of at least 50; the host's clock around the same calls beside it
+    n_lat = max(50, a.steps)
+    B.ts_profile_filter(model, "verify_pass")
+    B.ts_profile_enable(model, True)
+    pass_ms = []
     t0 = time.perf_counter()
-    for i in range(a.steps):
+    for i in range(n_lat):
         tok, par = trees[i % len(trees)]
         B.ts_verify(model, kv, tok, par)
-    verify_ms = (time.perf_counter() - t0) / a.steps * 1e3
+        pass_ms.append(B.ts_profile_read(model)["verify_pass"][1])
+    verify_wall_ms = (time.perf_counter() - t0) / n_lat * 1e3
+    B.ts_profile_enable(model, False)
+    B.ts_profile_filter(model, None)
+    verify_ms = float(np.median(pass_ms))
 
     # event-bracketed repeats: first the dominant kernel alone (its launches only, so the other
     # ~290 launches of a step run undisturbed), then every kernel kind for the breakdown table
@@ -298,11 +388,13 @@ def main():
     dom_bytes = 2 * cfg.d_ffn * cfg.d_model * 2            # gate + up weights, bf16, per launch
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
-    traffic = None
+    traffic = traffic_commit = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and a.workload == "w3":
         try:
-            traffic = json.load(open(tpath)).get(dom, {}).get("bytes")   # rocprofv3 counter passes, see profiles/
+            tj = json.load(open(tpath))
+            traffic = tj.get(dom, {}).get("bytes")          # rocprofv3 counter passes, see paper_2604_13519_amd/counters.py
+            traffic_commit = tj.get("_measured_on", {}).get("commit")
         except Exception:
             traffic = None
     total_bytes = algorithmic_bytes(cfg, P)
@@ -315,13 +407,15 @@ def main():
         "config": {"workload": desc, "context": P, "tree_nodes": int(len(trees[0][0])), "batch": 1,
                    "trees": "%d seeded trees cycled" % len(trees),
                    "storage": "bf16 weights and K/V cache; products in IEEE half, fp32 accumulation"},
-        "verify_ms": verify_ms, "commit_ms": ms_per_step - verify_ms,
+        "verify_ms": verify_ms, "verify_wall_ms": verify_wall_ms, "verify_passes_timed": n_lat,
+        "commit_ms": max(ms_per_step - verify_wall_ms, 0.0),
         "mean_tokens_per_step": emitted / a.steps,
         "step_algorithmic_gb": total_bytes / 1e9,
         "step_hbm_frac": total_bytes / (verify_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_frac_of_plain_read": total_bytes / (verify_ms * 1e-3) / (plain_bytes / (plain_us * 1e-6)),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_launch": dom_bytes,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_commit": traffic_commit,
+                     "bytes_per_launch": dom_bytes,
                      "avg_us": dom_us,
                      "plain_read": {"avg_us": plain_us, "GB/s": plain_bytes / (plain_us * 1e-6) / 1e9,
                                     "bytes_per_launch": plain_bytes, "launches": pn,

@@ -232,7 +232,9 @@ ts_status ts_kv_commit(ts_kv* kv);
 typedef struct { const char* name; int32_t launches; float total_ms; } ts_profile_entry;
 ts_status ts_profile_enable(ts_model* m, int32_t enable);
 /* Restrict the bracketing to launches of one kernel kind (e.g. "gemm_gate_up"), so that
- * its timing is not disturbed by events around every other launch; NULL = all kinds. */
+ * its timing is not disturbed by events around every other launch; NULL = all kinds.  The
+ * kind "verify_pass" brackets nothing but the whole pass of a verify call, from its first
+ * launch to the acceptance walk (one record per call; not part of the NULL set). */
 ts_status ts_profile_filter(ts_model* m, const char* kind_or_null);
 ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_entries, int32_t* n_entries);
 /* Reference point for the projections' bandwidth figures: `launches` launches of a kernel that

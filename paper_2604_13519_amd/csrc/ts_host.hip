@@ -716,6 +716,10 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   m->prof.clear();
   m->ev_used = 0;
   const int d = c.d_model, F = c.d_ffn;
+  // bracket of the whole pass (first launch .. acceptance walk), only when asked for by name
+  const bool time_pass = m->prof_on && m->prof_filter == "verify_pass";
+  if (time_pass) prof_begin(m, "verify_pass");
+  const size_t pass_rec = m->prof.size();
   launch_embed(m, dm, R);
   launch_rope_table(m, dm, R);
   int pending_parts = 0;          // split-K partials of the previous projection still to be added to H
@@ -778,6 +782,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   }
   if (sample) launch_sample(m, dm, R, n_seqs, sample->temperature, sample->seed);
   else launch_walk(m, dm, R, n_seqs);
+  if (time_pass && pass_rec >= 1) TS_HIP(hipEventRecord(m->prof[pass_rec - 1].b, m->stream));
   TS_HIP(hipGetLastError());
   for (int s = 0; s < n_seqs; ++s)
     TS_HIP(hipMemcpyAsync(m->res_host + (size_t)s * TS_RESULT_INTS, kvs[s]->result, TS_RESULT_INTS * 4, hipMemcpyDeviceToHost, m->stream));
