@@ -642,10 +642,15 @@ static RowMeta carve_meta(void* base, int rows) {
 // norm, lm_head, arg-max and walk, and leave no verify result behind (context ingestion).
 // sample: stochastic acceptance instead of the greedy walk (one sequence; logits are materialised).
 struct SampleArgs { float temperature; const float* node_uniform; uint64_t seed; };
+// Context ingestion runs several consecutive row blocks of ONE cache in a pass: block b is given
+// as a sequence of its own whose committed length (P) and root token are overridden - the rows of
+// the blocks before it are part of its context, which is exactly the causal mask.
+struct BlockOverride { const int32_t* P; const int32_t* root; };
 
 static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const int32_t* toks, const int32_t* pars,
                              const int32_t* offs, int32_t* accept_len, int32_t* acc_tokens, int32_t* acc_nodes,
-                             int32_t* bonus, bool ingest_only = false, const SampleArgs* sample = nullptr) {
+                             int32_t* bonus, bool ingest_only = false, const SampleArgs* sample = nullptr,
+                             const BlockOverride* blocks = nullptr) {
   const ts_model_config& c = m->cfg;
   const bool bf = c.dtype == TS_DTYPE_BF16;
   // ---- validation (nothing is modified before it passes) ---------------------------
@@ -655,14 +660,15 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     ts_kv* kv = kvs[s];
     if (!kv) return ts_fail(TS_ERR_INVALID_ARG, "null cache handle (sequence %d)", s);
     if (kv->model != m) return ts_fail(TS_ERR_INVALID_ARG, "cache %d belongs to another model", s);
-    for (int t = 0; t < s; ++t)
+    for (int t = 0; t < s && !blocks; ++t)
       if (kvs[t] == kv) return ts_fail(TS_ERR_INVALID_ARG, "cache handle used twice in one batch");
+    const int P_s = blocks ? blocks->P[s] : kv->P;
     const int n = offs[s + 1] - offs[s];
     if (n < 0 || n > TS_MAX_NODES) return ts_fail(TS_ERR_INVALID_TREE, "n_nodes %d outside [0,%d] (sequence %d)", n, TS_MAX_NODES, s);
     if (n > 0 && (!toks || !pars)) return ts_fail(TS_ERR_INVALID_ARG, "null draft arrays with n_nodes > 0");
-    if (kv->pending < 0) return ts_fail(TS_ERR_STATE, "no pending token (sequence %d): call ts_set_pending or commit a verify", s);
-    if (kv->P + n + 1 > kv->capacity)
-      return ts_fail(TS_ERR_KV_CAPACITY, "committed %d + tree rows %d exceed the capacity %d (sequence %d)", kv->P, n + 1, kv->capacity, s);
+    if (!blocks && kv->pending < 0) return ts_fail(TS_ERR_STATE, "no pending token (sequence %d): call ts_set_pending or commit a verify", s);
+    if (P_s + n + 1 > kv->capacity)
+      return ts_fail(TS_ERR_KV_CAPACITY, "committed %d + tree rows %d exceed the capacity %d (sequence %d)", P_s, n + 1, kv->capacity, s);
     for (int i = 0; i < n; ++i) {
       const int p = pars[offs[s] + i], t = toks[offs[s] + i];
       if (p < -1 || p >= i) return ts_fail(TS_ERR_INVALID_TREE, "parent_idx[%d] = %d outside [-1,%d) (sequence %d)", i, p, i, s);
@@ -670,8 +676,8 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
     }
     R += n + 1;
     max_M = std::max(max_M, n + 1);
-    max_keys = std::max(max_keys, kv->P + n + 1);
-    sum_keys += kv->P + n + 1;
+    max_keys = std::max(max_keys, P_s + n + 1);
+    sum_keys += P_s + n + 1;
   }
   if (!bf && (size_t)max_keys > attn_f32_max_keys())
     return ts_fail(TS_ERR_KV_CAPACITY, "fp32 path supports at most %zu keys per sequence", attn_f32_max_keys());
@@ -691,7 +697,8 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   for (int s = 0; s < n_seqs; ++s) {
     ts_kv* kv = kvs[s];
     const int n = offs[s + 1] - offs[s];
-    hm.tok[r0] = kv->pending; hm.pos[r0] = kv->P; hm.seq[r0] = s; hm.lrow[r0] = 0;
+    const int P_s = blocks ? blocks->P[s] : kv->P;
+    hm.tok[r0] = blocks ? blocks->root[s] : kv->pending; hm.pos[r0] = P_s; hm.seq[r0] = s; hm.lrow[r0] = 0;
     hm.par[r0] = -1; hm.depth[r0] = 0; hm.anc[r0] = 0; hm.u[r0] = 0.f;
     for (int i = 0; i < n; ++i) {
       const int r = r0 + i + 1;
@@ -699,12 +706,12 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
       hm.tok[r] = toks[offs[s] + i];
       hm.seq[r] = s; hm.lrow[r] = i + 1; hm.par[r] = prow;
       hm.depth[r] = hm.depth[r0 + prow] + 1;
-      hm.pos[r] = kv->P + hm.depth[r];
+      hm.pos[r] = P_s + hm.depth[r];
       hm.anc[r] = hm.anc[r0 + prow] | (1ull << i);
       hm.u[r] = sample ? sample->node_uniform[offs[s] + i] : 0.f;
     }
     SeqDesc& sd = hseq[s];
-    sd.P = kv->P; sd.M = n + 1; sd.row0 = r0; sd.n_pages = kv->n_pages;
+    sd.P = P_s; sd.M = n + 1; sd.row0 = r0; sd.n_pages = kv->n_pages;
     sd.page_table = kv->page_table; sd.k_pool = kv->k_pool; sd.v_pool = kv->v_pool; sd.result = kv->result;
     kv->have_result = false;
     r0 += n + 1;
@@ -892,19 +899,37 @@ extern "C" ts_status ts_prefill(ts_model* m, ts_kv* kv, const int32_t* tokens, i
   const int rows_total = (int)seq.size() - 1;
   if (kv->P + rows_total + 1 > kv->capacity)
     return ts_fail(TS_ERR_KV_CAPACITY, "committed %d + context %d + 1 exceed the capacity %d", kv->P, rows_total, kv->capacity);
-  int32_t chain_par[TS_MAX_NODES];
-  for (int i = 0; i < TS_MAX_NODES; ++i) chain_par[i] = i - 1;
+  // A pass ingests up to kPrefillBlocks consecutive row blocks of kPrefillRows rows.  Each block
+  // is a causal chain (root + 63 nodes: a chain's ancestor set is the causal mask) whose context
+  // is everything before it - the committed positions and the blocks in front of it in the same
+  // pass, whose K/V the pass writes before any attention launch of the layer reads them.
+  constexpr int kPrefillRows = 64, kPrefillBlocks = 16;
+  std::vector<int32_t> chain_par((size_t)kPrefillBlocks * (kPrefillRows - 1));
+  for (int b = 0; b < kPrefillBlocks; ++b)
+    for (int i = 0; i < kPrefillRows - 1; ++i) chain_par[(size_t)b * (kPrefillRows - 1) + i] = i - 1;
   const int saved_P = kv->P, saved_pending = kv->pending;
   int done = 0;
   while (done < rows_total) {
-    const int rows = std::min(rows_total - done, TS_MAX_NODES + 1);
-    kv->pending = seq[done];
-    const int32_t offs[2] = {0, rows - 1};
-    ts_kv* kvs[1] = {kv};
-    int32_t dummy_len = 0, dummy_bonus = 0;
-    ts_status st = verify_impl(m, kvs, 1, seq.data() + done + 1, chain_par, offs, &dummy_len, nullptr, nullptr, &dummy_bonus, true);
+    const int rows = std::min(rows_total - done, kPrefillRows * kPrefillBlocks);
+    const int n_blocks = (rows + kPrefillRows - 1) / kPrefillRows;
+    std::vector<int32_t> offs(n_blocks + 1, 0), blk_P(n_blocks), blk_root(n_blocks), nodes;
+    std::vector<ts_kv*> kvs(n_blocks, kv);
+    nodes.reserve(rows);
+    for (int b = 0; b < n_blocks; ++b) {
+      const int r0 = b * kPrefillRows, rb = std::min(rows - r0, kPrefillRows);
+      blk_P[b] = kv->P + r0;
+      blk_root[b] = seq[done + r0];
+      // only the last block can be short, so block b's nodes start at b * (kPrefillRows - 1),
+      // where chain_par restarts as well
+      nodes.insert(nodes.end(), seq.begin() + done + r0 + 1, seq.begin() + done + r0 + rb);
+      offs[b + 1] = offs[b] + rb - 1;
+    }
+    std::vector<int32_t> dummy_len(n_blocks), dummy_bonus(n_blocks);
+    const BlockOverride bo{blk_P.data(), blk_root.data()};
+    ts_status st = verify_impl(m, kvs.data(), n_blocks, nodes.data(), chain_par.data(), offs.data(), dummy_len.data(), nullptr,
+                               nullptr, dummy_bonus.data(), true, nullptr, &bo);
     if (st) { kv->P = saved_P; kv->pending = saved_pending; kv->have_result = false; return st; }
-    kv->P += rows;                                   // a chain's rows already sit in slots P .. P+rows-1
+    kv->P += rows;                                   // the rows already sit in slots P .. P+rows-1
     done += rows;
   }
   kv->pending = seq.back();
