@@ -25,9 +25,9 @@
  *    library copies and re-tiles them on the device; the caller may free its
  *    buffers as soon as ts_model_load returns.
  *
- * Tree conventions (paper App. A.1: drafts are "compacted into a single
- * flattened sequence" verified under a tree mask; dynamic trees adapt to each
- * draft's length, so any shape is legal):
+ * Tree conventions (paper App. A.1: all drafts of a step form one sequence that is
+ * verified under a tree mask; dynamic trees adapt to each draft's length, so any
+ * shape is legal):
  *  - The root of the tree is the PENDING token: the last emitted token, whose
  *    K/V are not in the cache yet.  It is not one of the n_nodes draft nodes.
  *  - parent_idx[i] is -1 (child of the root) or an index in [0, i): parents
@@ -73,11 +73,14 @@ enum { TS_MAX_NODES = 64, TS_PAGE_SIZE = 16 };
  * 1/sqrt(head_dim), SwiGLU feed-forward, no biases, untied embedding / lm_head.
  * dtype is the storage type of weights and KV cache.  TS_DTYPE_BF16 computes every
  * matrix product in IEEE half with fp32 accumulation (MFMA): the bf16 weights are
- * re-encoded as half once at load - exact, half has more significand bits; a finite
- * weight beyond half's range (|w| > 65504) makes ts_model_load fail with INVALID_ARG -
- * activations are rounded to half (saturating) where they enter a projection, bf16
- * K/V entries widen to half exactly, soft-max is fp32, and the residual stream and the
- * logits stay fp32.  It needs d_model, n_q_heads*head_dim and d_ffn to be multiples of
+ * re-encoded as half once at load - exact wherever half is normal (it has more
+ * significand bits); magnitudes below 2^-14 land on half's subnormal grid (absolute error
+ * below 3e-8), and a finite weight beyond half's range (|w| > 65504) makes ts_model_load
+ * fail with INVALID_ARG.  An activation that enters a projection is carried as the sum of
+ * two halves, hi = half(x) (saturating at 65504) and lo = half(x - hi), about 22
+ * significant bits; the rotated Q and the soft-max probabilities are single halves; bf16
+ * K/V entries widen to half exactly (same subnormal caveat); soft-max is fp32, and the
+ * residual stream and the logits stay fp32.  It needs d_model, n_q_heads*head_dim and d_ffn to be multiples of
  * 128 and head_dim 64 or 128.  TS_DTYPE_F32 computes in fp32. */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -119,6 +122,12 @@ ts_status ts_model_keep_logits(ts_model* m, int32_t enable);
  * host_logits: n_rows * vocab floats.  STATE if logits were not kept. */
 ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, float* host_logits);
 
+/* Number of projection inputs (normalised activations, attention outputs, SwiGLU products) whose
+ * magnitude exceeded the largest finite half (65504) and were clamped, summed over every pass
+ * since ts_model_load.  Non-zero means the model's activations left the range the bf16 path
+ * computes in and its results from that pass on are not those of the model; 0 for fp32 models. */
+ts_status ts_model_saturations(ts_model* m, uint64_t* count);
+
 /* The token each row of the most recent verify decided on, n_rows int32: after ts_verify /
  * ts_verify_batch the arg-max token of the row's logits as the fused lm_head epilogue found it
  * (lowest id among equal logits) - what the acceptance walk compared the row's children with;
@@ -139,6 +148,8 @@ ts_status ts_get_hidden(ts_model* m, int32_t row, float* host_hidden);
  * must cover the context plus the rows of the largest tree (n_nodes + 1).
  * Starts empty: length 0, no pending token. */
 ts_status ts_kv_alloc(ts_model* m, int32_t capacity_tokens, int32_t page_size, ts_kv** out);
+/* A cache refers to its model (stream, device): free every cache BEFORE ts_model_free of the
+ * model it was allocated on; freeing the model first leaves the cache handle dangling. */
 ts_status ts_kv_free(ts_kv* kv);
 /* Replace the identity page table by a permutation of [0, n_pages) (n_pages =
  * ceil(capacity/page_size)); only legal while the cache is empty. */
@@ -166,11 +177,10 @@ ts_status ts_kv_truncate(ts_kv* kv, int32_t new_len);
 
 /* Context ingestion (the context x of Alg. 1: prompts and tool documentation, Sec. 4.1) through
  * the verification kernels themselves: the sequence [pending token, if any] + tokens is run in
- * passes of up to 512 rows, each pass as consecutive causal chains of 64 rows (a chain's ancestor
+ * passes of up to 1024 rows, each pass as up to 16 consecutive causal chains of 64 rows (a chain's ancestor
  * set is the causal mask; the chains in front of it are part of its context), every row is kept
  * (the K/V of all but the last token are appended to the cache), the last token becomes the
- * pending token.  No logits are produced; the
- * next ts_verify scores the pending token.  Errors (state unchanged): INVALID_ARG, TOKEN_RANGE,
+ * pending token.  No logits are produced; the next ts_verify scores the pending token.  Errors (state unchanged): INVALID_ARG, TOKEN_RANGE,
  * KV_CAPACITY (committed + appended + 1 > capacity), DEVICE. */
 ts_status ts_prefill(ts_model* m, ts_kv* kv, const int32_t* tokens, int32_t n_tokens);
 
@@ -243,7 +253,7 @@ ts_status ts_profile_read(ts_model* m, ts_profile_entry* entries, int32_t max_en
  * only reads - launch i streams the fused gate/up weight tensor of layer i mod n_layers, the
  * bytes the largest projection of a step streams - on the model's stream, bracketed like any
  * other kind under the name "plain_read" (profiling must be on, and the filter, if set, must
- * name it).  The records join those of the most recent verify.  Returns after the launches
+ * name it).  bf16 models only (INVALID_ARG otherwise).  The records join those of the most recent verify.  Returns after the launches
  * have completed; bytes_per_launch (may be NULL) receives the tensor's size. */
 ts_status ts_profile_plain_read(ts_model* m, int32_t launches, uint64_t* bytes_per_launch);
 

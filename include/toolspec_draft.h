@@ -60,12 +60,12 @@ typedef struct {
   const int32_t* param_offsets;      /* param_first[n_tools] + 1                                 */
 } ts_schema_desc;
 
-/* Alg. 1, "Parse documentation into schema; construct the FSM".  INVALID_ARG on null or
+/* Alg. 1, the set-up steps: the schema (already parsed into token sequences) becomes the FSM.  INVALID_ARG on null or
  * inconsistent offsets, OOM. */
 ts_status ts_drafter_create(const ts_schema_desc* schema, ts_drafter** out);
 ts_status ts_drafter_free(ts_drafter* d);
 
-/* Alg. 1, "Retrieve historical calls" (Sec. 4.3): cosine similarity of h_x (dim floats) with
+/* Alg. 1, the retrieval step (Sec. 4.3, Eq. 3): cosine similarity of h_x (dim floats) with
  * the n_entries rows of H (row-major [n_entries][dim]), the k most similar kept in order of
  * decreasing similarity (equal similarity: lower index first; zero vectors have similarity
  * 0).  The tool-call outputs y_j are packed (y_tokens, y_offsets[n_entries + 1]); the drafter

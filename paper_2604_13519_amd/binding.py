@@ -20,7 +20,7 @@ TS_MAX_NODES, TS_PAGE_SIZE = 64, 16
 TS_Q_OTHERS, TS_Q_TOOL_NAME, TS_Q_PARAM_NAME, TS_Q_PARAM_VALUE = 0, 1, 2, 3
 TS_DRAFT_NONE, TS_DRAFT_RETRIEVAL, TS_DRAFT_SCHEMA = 0, 1, 2
 
-EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits", "ts_get_row_tokens", "ts_get_hidden",
+EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits", "ts_get_row_tokens", "ts_model_saturations", "ts_get_hidden",
            "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export", "ts_kv_export_noalloc",
            "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_sample", "ts_verify_batch",
            "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read", "ts_profile_plain_read",
@@ -93,6 +93,7 @@ def load_library(path=None):
         "ts_model_keep_logits": [C.c_void_p, C.c_int32],
         "ts_get_logits": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
         "ts_get_row_tokens": [C.c_void_p, C.c_int32, C.c_int32, i32p],
+        "ts_model_saturations": [C.c_void_p, C.POINTER(C.c_uint64)],
         "ts_get_hidden": [C.c_void_p, C.c_int32, C.c_void_p],
         "ts_kv_alloc": [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)],
         "ts_kv_free": [C.c_void_p],
@@ -192,6 +193,12 @@ def ts_get_logits(model, row0, n_rows, vocab):
     out = np.empty((n_rows, vocab), dtype=np.float32)
     _check(load_library().ts_get_logits(model, row0, n_rows, out.ctypes.data))
     return out
+
+
+def ts_model_saturations(model):
+    n = C.c_uint64()
+    _check(load_library().ts_model_saturations(model, C.byref(n)))
+    return int(n.value)
 
 
 def ts_get_row_tokens(model, row0, n_rows):

@@ -290,9 +290,11 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
 #pragma unroll
           for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[kt][mt][r]);
         mx = max_over_lane_groups(mx);
-        // the running reference is a whole number (scores in log2 units): rescaling by exact
-        // powers of two commutes with the bf16 rounding of the probabilities, so the result
-        // does not depend on how keys are blocked or split
+        // the running reference is a whole number (scores in log2 units) that follows the
+        // rounded-up maximum lazily (kRefSlack): every rescale is an exact power of two, which
+        // commutes with the half rounding of the probabilities, so blocking and splitting of the
+        // keys can change a probability only where it falls into half's subnormal range (below
+        // 2^-14 of the reference's scale)
         const float m_ceil = ceilf(mx * a.scale);
         const float m_new = (m_ceil > m_run[mt] + kRefSlack) ? m_ceil : m_run[mt];
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
@@ -371,7 +373,8 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
 constexpr int kMergeMaxSplits = 512;
 
 __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                    f16_t* __restrict__ Ab, size_t a_plane, int R, int Hq, int HD, int splits) {
+                                                    f16_t* __restrict__ Ab, size_t a_plane, int R, int Hq, int HD, int splits,
+                                                    unsigned long long* __restrict__ sat) {
   __shared__ float s_m[kMergeMaxSplits], s_l[kMergeMaxSplits];
   __shared__ float4 r_num[256];
   __shared__ float r_den[256];
@@ -428,7 +431,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__
     den += r_den[k * tpp + d4];
   }
   // the attention output feeds the O projection as a hi and a lo half
-  st_act_planes4(Ab + slot * HD + d4 * 4, a_plane, num.x / den, num.y / den, num.z / den, num.w / den);
+  st_act_planes4(Ab + slot * HD + d4 * 4, a_plane, num.x / den, num.y / den, num.z / den, num.w / den, sat);
 }
 
 // Rows are covered by RS waves per head, MT tiles of 16 rows each: (tiles -> RS x MT)
@@ -503,5 +506,5 @@ void launch_attn_merge(ts_model* m, int R, int splits) {
   ProfScope ps(m, "attn_merge");
   const ts_model_config& c = m->cfg;
   hipLaunchKernelGGL(k_attn_merge, dim3(R * c.n_q_heads), dim3(256), 0, m->stream, m->attn_part_o, m->attn_part_ml,
-                     (f16_t*)m->Ab, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * m->q_dim, R, c.n_q_heads, c.head_dim, splits);
+                     (f16_t*)m->Ab, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * m->q_dim, R, c.n_q_heads, c.head_dim, splits, m->sat_count);
 }

@@ -57,14 +57,25 @@ __device__ __forceinline__ void split_f16_planes(float x, _Float16& hi, _Float16
   hi = (_Float16)xs;
   lo = (_Float16)(xs - (float)hi);
 }
-__device__ __forceinline__ void st_act_planes(f16_t* p, size_t plane, float x) {
+// `sat` counts the activations whose magnitude exceeded the largest finite half and were clamped
+// (a model whose activations leave half's range is computed wrongly from there on: the caller can
+// see that it happened instead of getting silently clipped values)
+__device__ __forceinline__ void count_saturated(float x, unsigned long long* sat) {
+  if (fabsf(x) > 65504.f) atomicAdd(sat, 1ull);
+}
+__device__ __forceinline__ void st_act_planes(f16_t* p, size_t plane, float x, unsigned long long* sat) {
   _Float16 hi, lo;
+  count_saturated(x, sat);
   split_f16_planes(x, hi, lo);
   p[0] = __builtin_bit_cast(uint16_t, hi);
   p[plane] = __builtin_bit_cast(uint16_t, lo);
 }
 // four consecutive activations (p 8-byte aligned): one vector store per plane
-__device__ __forceinline__ void st_act_planes4(f16_t* p, size_t plane, float x0, float x1, float x2, float x3) {
+__device__ __forceinline__ void st_act_planes4(f16_t* p, size_t plane, float x0, float x1, float x2, float x3,
+                                               unsigned long long* sat) {
+  if (fmaxf(fmaxf(fabsf(x0), fabsf(x1)), fmaxf(fabsf(x2), fabsf(x3))) > 65504.f) {
+    count_saturated(x0, sat); count_saturated(x1, sat); count_saturated(x2, sat); count_saturated(x3, sat);
+  }
   _Float16 h[4], l[4];
   split_f16_planes(x0, h[0], l[0]);
   split_f16_planes(x1, h[1], l[1]);

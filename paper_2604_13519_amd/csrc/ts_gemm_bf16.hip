@@ -46,6 +46,7 @@ struct GemmArgs {
   int32_t* aidx;
   f16_t* act_out;      // SWIGLU: [2 planes][rows][N/2] gated product, IEEE half hi + lo
   size_t act_plane;    // elements between its planes
+  unsigned long long* sat;   // counts gated products beyond half's range
   int R, N, K;
   int kper;            // k elements per split
   int n_tiles;         // ceil(N / 16)
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(64 * CS * KW) void k_gemm_bf16(GemmArgs a) {
         const int f = (nt_idx[0] >> 1) * 16 + l15;           // tiles 2j / 2j+1 = gate / up of features 16j..
         if (nt_idx[1] < a.n_tiles) {
           const float gv = v[0], uv = v[NT - 1];
-          st_act_planes(a.act_out + (size_t)row * (a.N / 2) + f, a.act_plane, gv / (1.0f + expf(-gv)) * uv);
+          st_act_planes(a.act_out + (size_t)row * (a.N / 2) + f, a.act_plane, gv / (1.0f + expf(-gv)) * uv, a.sat);
         }
       } else {
         float* o = a.out + (size_t)blockIdx.y * a.split_stride;
@@ -394,6 +395,7 @@ void launch_gemm_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* out, 
   a.act_plane = (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * (N / 2);
   a.aval = m->amax_val; a.aidx = m->amax_idx;
   a.act_out = act_out;
+  a.sat = m->sat_count;
   a.R = R; a.N = N; a.K = K;
   const int splits = mode == MODE_PARTIAL ? plan.splits : 1;
   a.kper = K / splits;

@@ -35,6 +35,7 @@ struct RowsArgs {
   const f16_t* X;      // [2 planes][x_rows][K] IEEE half (x = hi + lo)
   size_t x_plane;      // elements between the planes
   size_t act_plane;    // SWIGLU: elements between the planes of act_out
+  unsigned long long* sat;   // counts gated products beyond half's range
   int x_rows;          // rows allocated (reads are clamped to them)
   const f16_t* Wt;     // tiled weights, IEEE half
   float* out;          // [split][R][N] partial sums
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
         if (nt_idx[t + 1] < a.n_tiles) {
           const int f = (nt_idx[t] >> 1) * 16 + l15;
           const float gv = v[t], uv = v[t + 1];
-          st_act_planes(a.act_out + (size_t)row * (a.N / 2) + f, a.act_plane, gv / (1.0f + expf(-gv)) * uv);
+          st_act_planes(a.act_out + (size_t)row * (a.N / 2) + f, a.act_plane, gv / (1.0f + expf(-gv)) * uv, a.sat);
         }
       }
     } else {
@@ -364,6 +365,7 @@ void launch_gemm_rows_bf16(ts_model* m, const f16_t* X, const f16_t* Wt, float* 
   a.x_plane = (size_t)a.x_rows * K;
   a.act_plane = (size_t)a.x_rows * (N / 2);
   a.act_out = act_out;
+  a.sat = m->sat_count;
   a.logits = logits; a.aval = m->amax_val; a.aidx = m->amax_idx; a.amax_stride = m->amax_parts;
   a.R = R; a.N = N; a.K = K;
   if (mode != MODE_PARTIAL) splits = 1;

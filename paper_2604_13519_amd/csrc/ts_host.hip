@@ -3,6 +3,7 @@
 // All arithmetic of the pass runs in the kernels; the host only validates the tree,
 // derives per-row bookkeeping (depth, position, ancestor bit set) and orders launches.
 #include <stdarg.h>
+#include <stdlib.h>
 #include <stdio.h>
 #include <string.h>
 
@@ -11,6 +12,7 @@
 #include <new>
 
 #include "ts_internal.h"
+#include "ts_device_utils.h"
 
 // ---------------------------------------------------------------------------------
 // errors
@@ -293,6 +295,7 @@ static ts_status model_load_impl(ts_model* m, const ts_weights* w) {
     big = std::max(big, (size_t)m->q_dim * d);
     if ((st = dev_alloc_bytes(&staging, big * 2, false))) return st;
     if ((st = dev_alloc_bytes((void**)&m->range_flag, sizeof(int), true))) { dev_free(staging); return st; }
+    if ((st = dev_alloc_bytes((void**)&m->sat_count, sizeof(unsigned long long), true))) { dev_free(staging); return st; }
   }
   auto matrix_bytes = [&](int N, int K) { return (bf ? tiled_elems(N, K) : (size_t)N * K) * esz; };
 
@@ -355,7 +358,7 @@ extern "C" ts_status ts_model_free(ts_model* m) {
   (void)hipSetDevice(m->device);
   if (m->stream) (void)hipStreamSynchronize(m->stream);
   free_workspace(m);
-  dev_free(m->embed); dev_free(m->lm_head); dev_free(m->norm_f); dev_free(m->range_flag);
+  dev_free(m->embed); dev_free(m->lm_head); dev_free(m->norm_f); dev_free(m->range_flag); dev_free(m->sat_count);
   for (LayerW& L : m->layers) {
     dev_free(L.wqkv); dev_free(L.wo); dev_free(L.wgu); dev_free(L.wd); dev_free(L.norm1); dev_free(L.norm2);
   }
@@ -378,7 +381,7 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   m->kv_dim = cfg->n_kv_heads * cfg->head_dim;
   m->qkv_dim = m->q_dim + 2 * m->kv_dim;
   m->stream = nullptr;
-  m->embed = m->lm_head = nullptr; m->norm_f = nullptr; m->range_flag = nullptr;
+  m->embed = m->lm_head = nullptr; m->norm_f = nullptr; m->range_flag = nullptr; m->sat_count = nullptr;
   m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr; m->part_elems = 0;
   m->attn_part_o = nullptr; m->attn_part_ml = nullptr; m->attn_max_splits = 0;
   m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr; m->logits = nullptr;
@@ -439,6 +442,17 @@ extern "C" ts_status ts_get_logits(ts_model* m, int32_t row0, int32_t n_rows, fl
   (void)hipSetDevice(m->device);
   TS_HIP(hipStreamSynchronize(m->stream));
   TS_HIP(copy_sync(m->stream, host, m->logits + (size_t)row0 * m->cfg.vocab, (size_t)n_rows * m->cfg.vocab * 4, hipMemcpyDeviceToHost));
+  return TS_OK;
+}
+
+extern "C" ts_status ts_model_saturations(ts_model* m, uint64_t* count) {
+  if (!m || !count) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  *count = 0;
+  if (!m->sat_count) return TS_OK;                 // fp32 models have no half-precision projection inputs
+  (void)hipSetDevice(m->device);
+  unsigned long long v = 0;
+  TS_HIP(copy_sync(m->stream, &v, m->sat_count, sizeof(v), hipMemcpyDeviceToHost));
+  *count = (uint64_t)v;
   return TS_OK;
 }
 
@@ -979,8 +993,11 @@ extern "C" ts_status ts_profile_filter(ts_model* m, const char* kind) {
 extern "C" ts_status ts_profile_plain_read(ts_model* m, int32_t launches, uint64_t* bytes_per_launch) {
   if (!m || launches < 0) return ts_fail(TS_ERR_INVALID_ARG, "null model or negative launch count");
   if (m->layers.empty()) return ts_fail(TS_ERR_STATE, "model has no layers");
+  // the kernel's never-taken store needs a valid sink word: bf16 models own one (range_flag)
+  if (m->cfg.dtype != TS_DTYPE_BF16 || !m->range_flag)
+    return ts_fail(TS_ERR_INVALID_ARG, "ts_profile_plain_read: bf16 models only");
   (void)hipSetDevice(m->device);
-  const size_t bytes = (size_t)2 * m->cfg.d_ffn * m->cfg.d_model * (m->esz == 2 ? 2 : 4);
+  const size_t bytes = (size_t)2 * m->cfg.d_ffn * m->cfg.d_model * 2;
   for (int i = 0; i < launches; ++i)
     launch_plain_read(m, m->layers[i % m->layers.size()].wgu, bytes, (uint32_t*)m->range_flag);
   TS_HIP(hipGetLastError());

@@ -84,6 +84,7 @@ struct ts_model {
   void* lm_head;                // device, tiled (bf16) or row-major (f32)
   float* norm_f;
   int* range_flag;              // device; set by the weight re-tiling when a weight does not fit IEEE half
+  unsigned long long* sat_count;   // device; projection inputs clamped to half's range since load (bf16 models)
   std::vector<LayerW> layers;
   // workspace, sized for ws_rows rows (multiple of TS_MROWS_PER_BLOCK)
   int ws_rows, ws_seqs;

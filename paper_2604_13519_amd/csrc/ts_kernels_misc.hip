@@ -14,11 +14,11 @@ __device__ __forceinline__ void st_q(bf16_t* p, float v) { *p = f32_to_f16_bits(
 
 // store an activation that feeds a projection: float as is; for bf16 models as a hi and a lo
 // IEEE half in two planes `plane` elements apart (hi saturating)
-__device__ __forceinline__ void st_act(float* p, size_t, float v) { *p = v; }
-__device__ __forceinline__ void st_act(f16_t* p, size_t plane, float v) { st_act_planes(p, plane, v); }
+__device__ __forceinline__ void st_act(float* p, size_t, float v, unsigned long long*) { *p = v; }
+__device__ __forceinline__ void st_act(f16_t* p, size_t plane, float v, unsigned long long* sat) { st_act_planes(p, plane, v, sat); }
 // four consecutive activations (p 16-byte aligned in float terms): one vector store per plane
-__device__ __forceinline__ void st_act4(float* p, size_t, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
-__device__ __forceinline__ void st_act4(f16_t* p, size_t plane, const float4& v) { st_act_planes4(p, plane, v.x, v.y, v.z, v.w); }
+__device__ __forceinline__ void st_act4(float* p, size_t, const float4& v, unsigned long long*) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st_act4(f16_t* p, size_t plane, const float4& v, unsigned long long* sat) { st_act_planes4(p, plane, v.x, v.y, v.z, v.w, sat); }
 
 // ---------------------------------------------------------------------------------
 // weight re-tiling (model load): row-major [N][K] bf16 -> MFMA operand tiles of IEEE half.
@@ -113,7 +113,8 @@ void launch_rope_table(ts_model* m, const RowMeta& rm, int R) {
 template <typename T>
 __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const float* __restrict__ part, int n_parts,
                                                size_t part_stride, const float* __restrict__ gain,
-                                               T* __restrict__ Xn, size_t x_plane, int d, float eps) {
+                                               T* __restrict__ Xn, size_t x_plane, int d, float eps,
+                                               unsigned long long* __restrict__ sat) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   float4* h4 = reinterpret_cast<float4*>(H + (size_t)r * d);
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(1024) void k_norm(float* __restrict__ H, const floa
   for (int w = 0; w < 16; ++w) tot += red[w];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
   auto emit = [&](int i, const float4& v, const float4& g) {
-    st_act4(Xn + (size_t)r * d + 4 * i, x_plane, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w));
+    st_act4(Xn + (size_t)r * d + 4 * i, x_plane, make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w), sat);
   };
 #pragma unroll
   for (int k = 0; k < KEEP; ++k) {
@@ -171,10 +172,10 @@ void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part
   ProfScope ps(m, "residual_rmsnorm");
   if (m->cfg.dtype == TS_DTYPE_BF16)
     hipLaunchKernelGGL(k_norm<f16_t>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (f16_t*)m->Xn, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * m->cfg.d_model, m->cfg.d_model, m->cfg.rms_eps);
+                       (f16_t*)m->Xn, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * m->cfg.d_model, m->cfg.d_model, m->cfg.rms_eps, m->sat_count);
   else
     hipLaunchKernelGGL(k_norm<float>, dim3(R), dim3(1024), 0, m->stream, m->H, m->part, n_parts, part_stride, gain,
-                       (float*)m->Xn, (size_t)0, m->cfg.d_model, m->cfg.rms_eps);
+                       (float*)m->Xn, (size_t)0, m->cfg.d_model, m->cfg.rms_eps, (unsigned long long*)nullptr);
 }
 
 // ---------------------------------------------------------------------------------
@@ -249,7 +250,7 @@ void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_part
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t part_stride, T* __restrict__ Fb,
-                         size_t f_plane, int R, int F) {
+                         size_t f_plane, int R, int F, unsigned long long* __restrict__ sat) {
   const size_t total = (size_t)R * F;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int r = (int)(i / F), f = (int)(i % F);
@@ -260,7 +261,7 @@ __global__ void k_swiglu(const float* __restrict__ part, int n_parts, size_t par
       g += p[(size_t)s * part_stride];
       u += p[(size_t)s * part_stride + 16];
     }
-    st_act(Fb + i, f_plane, g / (1.0f + expf(-g)) * u);
+    st_act(Fb + i, f_plane, g / (1.0f + expf(-g)) * u, sat);
   }
 }
 
@@ -271,9 +272,9 @@ void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride) {
   int blocks = (int)((total + 255) / 256);
   if (blocks > 4096) blocks = 4096;
   if (m->cfg.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_swiglu<f16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (f16_t*)m->Fb, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * F, R, F);
+    hipLaunchKernelGGL(k_swiglu<f16_t>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (f16_t*)m->Fb, (size_t)(m->ws_rows + TS_MROWS_PER_BLOCK) * F, R, F, m->sat_count);
   else
-    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, (size_t)0, R, F);
+    hipLaunchKernelGGL(k_swiglu<float>, dim3(blocks), dim3(256), 0, m->stream, m->part, n_parts, part_stride, (float*)m->Fb, (size_t)0, R, F, (unsigned long long*)nullptr);
 }
 
 // ---------------------------------------------------------------------------------

@@ -11,8 +11,9 @@ App. B.3; near-tied logits are exempt).
 
 Calls only oracle/ and the seeded input generators in workloads/.
 
-Usage: python tests/golden/make_decision_sweep.py [model] [n_trees] [first_tree]
-       (appends to an existing file when first_tree > 0)
+Usage: python tests/golden/make_decision_sweep.py [model] [n_trees] [first_tree] [output file]
+       (appends to an existing file when first_tree > 0; the default output is
+       tests/golden/decisions_<model>.txt)
 """
 import os
 import sys
@@ -47,8 +48,8 @@ def main():
     w = {k: gen_tensor(cfg, 1234, k) for k in ("embed", "lm_head", "norm_f")}
     w["layers"] = lambda l: LazyLayer(cfg, l)
     model = O.OracleModel(cfg, w, cache=True)
-    path = os.path.join(HERE, "decisions_%s.txt" % name)
-    if first == 0:
+    path = sys.argv[4] if len(sys.argv) > 4 else os.path.join(HERE, "decisions_%s.txt" % name)
+    if first == 0 or not os.path.exists(path):
         with open(path, "w") as f:
             f.write("# CPU oracle decisions on the arg-max decision sweep, model %s, weights seed 1234,\n" % name)
             f.write("# case t = workloads.decision_sweep_case(cfg, t, P=%d, n_nodes=64); 65 rows per case.\n" % P)

@@ -16,7 +16,9 @@ comparison of the accepted path.
 
 Calls only oracle/ and the seeded input generators in workloads/.
 
-Usage: python tests/golden/make_w5_expected.py [greedy_steps]
+Usage: python tests/golden/make_w5_expected.py [greedy_steps] [output file] [greedy side file]
+       (the greedy continuation is appended to the side file, tests/golden/w5_greedy.txt by default,
+       step by step; a run that finds it complete goes straight to the tree passes)
 """
 import os
 import sys
@@ -43,6 +45,8 @@ class LazyLayer:
         self.cfg, self.layer = cfg, layer
 
     def __getitem__(self, kind):
+        if kind == "norm1" and self.layer % 8 == 0:
+            print("  layer %d" % self.layer, flush=True)
         return gen_tensor(self.cfg, 1234, kind, self.layer)
 
 
@@ -89,16 +93,34 @@ def main():
     root = wl.root_token(cfg.vocab, P, seed=3456 + REQ)
     print("context generated (%.0f s)" % (time.time() - t0), flush=True)
 
+    # the greedy continuation is kept in a side file as it grows, so that an interrupted run resumes
+    path = sys.argv[2] if len(sys.argv) > 2 else os.path.join(HERE, "w5_expected.txt")
+    side = sys.argv[3] if len(sys.argv) > 3 else os.path.join(HERE, "w5_greedy.txt")
+    greedy, gmargin = [], []
+    if os.path.exists(side):
+        for line in open(side):
+            t, mg = line.split()
+            greedy.append(int(t))
+            gmargin.append(float(mg))
+        print("resuming after %d stored greedy steps" % len(greedy), flush=True)
     kv = LazyKV(cfg, K16, V16, root)
     empty = np.zeros(0, np.int32)
-    greedy, gmargin = [], []
-    for i in range(greedy_steps):
+    for i in range(greedy_steps if len(greedy) < greedy_steps else 0):   # all steps stored: nothing to replay
+        if i < len(greedy):
+            # replay a stored step: the pass is needed anyway for the K/V of the committed token
+            r = O.verify(model, kv, np.zeros(0, np.int32), np.zeros(0, np.int32), "R")
+            assert r.bonus_token == greedy[i]
+            O.commit(kv, r)
+            continue
         r = O.verify(model, kv, empty, empty, "R")
         O.commit(kv, r)
         greedy.append(r.bonus_token)
         gmargin.append(float(r.margin[0]))
+        with open(side, "a") as f:
+            f.write("%d %.6e\n" % (r.bonus_token, r.margin[0]))
         print("greedy step %d: token %d margin %.4f (%.0f s)" % (i + 1, r.bonus_token, r.margin[0], time.time() - t0), flush=True)
 
+    greedy, gmargin = greedy[:greedy_steps], gmargin[:greedy_steps]
     tok, par = wl.schema_retrieval_tree(greedy, cfg.vocab, np.random.default_rng([3456, 5, REQ]))
     kv = LazyKV(cfg, K16, V16, root)
     res = {}
@@ -108,7 +130,6 @@ def main():
 
     rng = np.random.default_rng([99, REQ])
     extra = rng.choice(cfg.vocab, size=N_SAMPLE, replace=False)
-    path = os.path.join(HERE, "w5_expected.txt")
     with open(path, "w") as f:
         f.write("# CPU oracle, 32B-class shape at full depth (config %s, weights seed 1234), request %d of the batch:\n" % (CFG, REQ))
         f.write("# context K/V seed %d, P = %d, root token %d.  Written by tests/golden/make_w5_expected.py\n" % (2345 + REQ, P, root))

@@ -429,6 +429,34 @@ def test_many_row_projection_row_counts(cfg_name, total_rows):
 # ------------------------------------------------------------------------------------
 # boundary: error paths (forced from the host; every kernel still exits normally)
 # ------------------------------------------------------------------------------------
+def test_saturated_projection_inputs_are_counted_not_hidden():
+    """Activations beyond the largest finite half are clamped AND counted: an ordinary model
+    reports 0 after a pass, a model whose first norm gain is blown up reports many."""
+    cfg = wl.get_config("small_bf16")
+    w = wl.gen_weights(cfg, 1234)
+    rng = np.random.default_rng(8)
+    K, V = wl.gen_context_kv(cfg, 40, seed=3)
+    tok, par = _random_tree(rng, 20, cfg.vocab)
+    counts = []
+    for gain in (None, 3.0e5):
+        ww = dict(w)
+        ww["layers"] = [dict(l) for l in w["layers"]]
+        if gain is not None:
+            ww["layers"][0]["norm1"] = wl.f32_to_bf16_bits(np.full(cfg.d_model, gain, np.float32))
+        model = B.ts_model_load(cfg, ww)
+        kv = B.ts_kv_alloc(model, 120)
+        try:
+            B.ts_kv_import(kv, K, V)
+            B.ts_set_pending(kv, 5)
+            assert B.ts_model_saturations(model) == 0
+            B.ts_verify(model, kv, tok, par)
+            counts.append(B.ts_model_saturations(model))
+        finally:
+            B.ts_kv_free(kv)
+            B.ts_model_free(model)
+    assert counts[0] == 0 and counts[1] > 100, counts
+
+
 def test_weight_beyond_half_range_fails_the_load():
     """bf16 models multiply in IEEE half: a finite weight that half cannot hold (|w| > 65504) must
     make ts_model_load fail instead of becoming an infinity; the largest finite half still loads."""
