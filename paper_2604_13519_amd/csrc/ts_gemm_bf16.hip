@@ -304,14 +304,12 @@ void launch_mt(int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
 // The compiled tile shapes.  shape id -> (NT, CS, KW): tiles per wave, column sets and
 // k-waves per workgroup.  All use chunks of 128 k (the LDS holds two buffers of the
 // activation chunk, 43 KiB for 80 rows).  The k-wave shapes hold fewer weight registers
-// per chunk and prefetch two chunks ahead instead of one.  Shape 5 (96 columns, 6 waves) exists
-// because 6144 output features (the 8B QKV projection) fill 256 CUs as 64 groups x 4 splits
-// but only 192 as 48 x 4.
-constexpr int kNumShapes = 6;
-const int kShapeNT[kNumShapes] = {1, 2, 1, 2, 2, 2};
-const int kShapeCS[kNumShapes] = {4, 4, 8, 8, 4, 3};
-const int kShapeKW[kNumShapes] = {1, 1, 1, 1, 2, 2};
-const int kShapeKC[kNumShapes] = {128, 128, 128, 128, 128, 128};
+// per chunk and prefetch two chunks ahead instead of one.
+constexpr int kNumShapes = 5;
+const int kShapeNT[kNumShapes] = {1, 2, 1, 2, 2};
+const int kShapeCS[kNumShapes] = {4, 4, 8, 8, 4};
+const int kShapeKW[kNumShapes] = {1, 1, 1, 1, 2};
+const int kShapeKC[kNumShapes] = {128, 128, 128, 128, 128};
 
 template <int MODE>
 void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a) {
@@ -321,7 +319,6 @@ void launch_shape(int shape, int mt, dim3 grid, hipStream_t s, const GemmArgs& a
     case 2: if (MODE != MODE_SWIGLU) launch_mt<1, 8, 1, 128, 1, MODE == MODE_SWIGLU ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
     case 3: launch_mt<2, 8, 1, 128, 1, MODE>(mt, grid, s, a); break;
     case 4: if (MODE != MODE_ARGMAX) launch_mt<2, 4, 2, 128, 2, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
-    case 5: if (MODE != MODE_ARGMAX) launch_mt<2, 3, 2, 128, 2, MODE == MODE_ARGMAX ? MODE_PARTIAL : MODE>(mt, grid, s, a); break;
     default: break;
   }
 }
@@ -344,7 +341,7 @@ int gemm_bf16_chunk(int shape) { return shape >= kRowsShape0 ? gemm_rows_chunk((
 // Tile shape and cross-workgroup K splits, from a byte count per CU:
 //   rounds x (weight bytes one workgroup streams)         rounds = ceil(workgroups / CUs)
 // + write and read of the fp32 partial sums, shared by all CUs (only if splits > 1)
-// + a quarter of the activation bytes a workgroup stages from L2 per round.
+// + a quarter of the activation bytes (both planes) a workgroup stages from L2 per round.
 // Measured on MI355X, a second round of workgroups costs a full round (the tail does not
 // overlap), which the round count models.  mode: 0 partial sums, 1 arg-max (no split),
 // 2 SwiGLU epilogue (no split).
@@ -373,8 +370,12 @@ GemmPlan gemm_bf16_plan(const ts_model* m, int R, int N, int K, int mode) {
       const double kper = (double)K / s;
       double cost = rounds * cols * kper * 2.0;
       if (s > 1) cost += 2.0 * s * R * (double)N * 4.0 / m->n_cu;
-      cost += 0.25 * rounds * rows * kper * 2.0;
-      if (kShapeCS[shape] * kShapeKW[shape] < 6) cost *= 1.05;   // 4-wave workgroups hide less latency
+      cost += 0.25 * rounds * rows * kper * 2.0 * TS_ACT_PLANES;
+      // Measured (8B shape, 65 rows): over a long K range the k-wave shape wins by its deeper prefetch
+      // (gate/up, 32 chunks: 56.2 us against 58.1 us for the 4-wave shape of the same columns); over
+      // the short ranges of the split projections its longer prologue and the cross-wave reduction
+      // are not amortised (O, 4 chunks: 17.0 against 15.2 us; QKV, 8 chunks: 21.9 against 21.2 us).
+      if (kper / kc >= 16 ? kShapeCS[shape] * kShapeKW[shape] < 6 : kShapeKW[shape] > 1) cost *= 1.05;
       if (kShapeNT[shape] < 2) cost *= 1.05;                     // one tile per wave reads twice the LDS per weight byte
       if (cost < best_cost) { best_cost = cost; best.shape = shape; best.splits = s; }
     }

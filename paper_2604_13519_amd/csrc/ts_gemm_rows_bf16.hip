@@ -24,6 +24,7 @@
 #include "ts_internal.h"
 #include "ts_device_utils.h"
 #include <algorithm>
+#include <type_traits>
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -118,27 +119,37 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  f16x8 w[2][NT][KSW];
-  u32x4 xr[XPT];
+  // Pipeline depth.  With one workgroup per CU (2 waves per SIMD) the loads need more than one
+  // chunk of matrix-core time to arrive: weights travel RD - 1 chunks ahead in a register ring,
+  // activations XD chunks ahead in registers and one chunk ahead in LDS.  The 4-row-tile kernels
+  // that run two workgroups per CU keep the short pipeline (their register budget is half).
+  constexpr int RD = (MT <= 4 && KW <= 2) ? 2 : 4;
+  constexpr int XD = (RD == 4 && KW == 1) ? 2 : 1;
+  f16x8 w[RD][NT][KSW];
+  u32x4 xr[XD][XPT];
+  const int last_chunk = n_chunks - 1;
 
+  // loads are never predicated (a load under an `if` would make every later wait a wait for
+  // everything): past the end they re-request the last chunk
   auto load_w = [&](f16x8 (&dst)[NT][KSW], int chunk) {
+    const size_t off = (size_t)min(chunk, last_chunk) * (KSTEPS * 1024);
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int j = 0; j < KSW; ++j)
-        dst[t][j] = *reinterpret_cast<const f16x8*>(wbase[t] + (size_t)chunk * (KSTEPS * 1024) + w_lane + j * 1024);
+        dst[t][j] = *reinterpret_cast<const f16x8*>(wbase[t] + off + w_lane + j * 1024);
   };
-  auto load_x = [&](int chunk) {
-    const char* xb = xbase + (size_t)chunk * (KC * 2);
+  auto load_x = [&](u32x4 (&dst)[XPT], int chunk) {
+    const char* xb = xbase + (size_t)min(chunk, last_chunk) * (KC * 2);
 #pragma unroll
-    for (int p = 0; p < XPT; ++p) xr[p] = *reinterpret_cast<const u32x4*>(xb + x_off[p]);
+    for (int p = 0; p < XPT; ++p) dst[p] = *reinterpret_cast<const u32x4*>(xb + x_off[p]);
   };
-  auto store_x = [&](int buf) {
+  auto store_x = [&](const u32x4 (&src)[XPT], int buf) {
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
       const int v = tid + p * NTHR;
       if (XV % NTHR == 0 || v < XV)
-        *reinterpret_cast<u32x4*>(&xs[buf][v / XVP][(v % XVP) / (KC / 8)][(v % (KC / 8)) * 8]) = xr[p];
+        *reinterpret_cast<u32x4*>(&xs[buf][v / XVP][(v % XVP) / (KC / 8)][(v % (KC / 8)) * 8]) = src[p];
     }
   };
   auto mma_chunk = [&](const f16x8 (&wc)[NT][KSW], int buf) {
@@ -156,26 +167,36 @@ __global__ __launch_bounds__(64 * WAVES) void k_gemm_rows_bf16(RowsArgs a) {
       }
     }
   };
-  auto step = [&](f16x8 (&wcur)[NT][KSW], f16x8 (&wnext)[NT][KSW], int c, bool steady) {
-    const bool more = steady || c + 1 < n_chunks;
-    if (more) { load_x(c + 1); load_w(wnext, c + 1); }
-    mma_chunk(wcur, c & 1);
-    if (more) store_x((c + 1) & 1);
+  // Step c (I = c % RD at compile time).  On entry: weights of chunks c .. c+RD-2 requested,
+  // activations of chunk c in LDS buffer c % 2, of chunks c+1 .. c+XD-1 requested into registers.
+  auto step = [&](auto i_c, int c) {
+    constexpr int I = decltype(i_c)::value;
+    load_x(xr[I % XD], c + XD);
+    load_w(w[(I + RD - 1) % RD], c + RD - 1);
+    mma_chunk(w[I], I & 1);
+    store_x(xr[(I + 1) % XD], (I + 1) & 1);
     __syncthreads();
   };
 
-  load_x(0);
-  load_w(w[0], 0);
-  store_x(0);
+#pragma unroll
+  for (int i = 0; i < XD; ++i) load_x(xr[i], i);
+#pragma unroll
+  for (int i = 0; i < RD - 1; ++i) load_w(w[i], i);
+  store_x(xr[0], 0);
   __syncthreads();
   int c0 = 0;
-  for (; c0 + 3 <= n_chunks; c0 += 2) {
-    step(w[0], w[1], c0, true);
-    step(w[1], w[0], c0 + 1, true);
+  for (; c0 + RD <= n_chunks; c0 += RD) {
+    step(std::integral_constant<int, 0>{}, c0);
+    step(std::integral_constant<int, 1>{}, c0 + 1);
+    if (RD == 4) {
+      step(std::integral_constant<int, 2 % RD>{}, c0 + 2);
+      step(std::integral_constant<int, 3 % RD>{}, c0 + 3);
+    }
   }
-  for (; c0 < n_chunks; c0 += 2) {
-    step(w[0], w[1], c0, false);
-    if (c0 + 1 < n_chunks) step(w[1], w[0], c0 + 1, false);
+  if (c0 < n_chunks) step(std::integral_constant<int, 0>{}, c0);
+  if (RD == 4) {
+    if (c0 + 1 < n_chunks) step(std::integral_constant<int, 1>{}, c0 + 1);
+    if (c0 + 2 < n_chunks) step(std::integral_constant<int, 2 % RD>{}, c0 + 2);
   }
 
   if (MODE == MODE_ARGMAX) {
@@ -344,9 +365,10 @@ bool gemm_rows_plan(const ts_model* m, int R, int N, int K, int mode, size_t max
         const int wg_per_cu = (cfg <= 1 && mt <= 4) ? 2 : 1;
         const long rounds = (wgs + (long)m->n_cu * wg_per_cu - 1) / ((long)m->n_cu * wg_per_cu);
         // MFMAs a SIMD issues for one workgroup (2 waves per SIMD), 16 cycles each at 2.4 GHz;
-        // measured issue efficiency: about 0.36 with four waves per SIMD, 0.30 with two, a tenth
-        // less with four k-waves
-        const double eff = (wg_per_cu == 2 ? 0.36 : 0.30) * (cfg == 2 ? 0.9 : 1.0);
+        // measured issue efficiency (one activation plane's worth): about 0.36 with four waves per
+        // SIMD and the short pipeline, 0.40 with two waves and the deep one, a tenth less with k-waves
+        // (their deeper activation registers leave no room for two chunks ahead)
+        const double eff = wg_per_cu == 2 ? 0.36 : (cfg == 0 ? 0.40 : 0.36 * (cfg == 2 ? 0.9 : 1.0));
         const double mfma_us = 2.0 * (K / s / 32 / kCfgKW[cfg]) * mt * NT * 16 / 2400.0;
         double cost = rounds * (wg_per_cu * mfma_us / eff + 6.0);
         if (s > 1) cost += s * R * (double)N * 4.0 / 12.0e6;        // partial sums, mostly overlapped with the products
