@@ -177,7 +177,7 @@ ts_status ts_kv_truncate(ts_kv* kv, int32_t new_len);
 
 /* Context ingestion (the context x of Alg. 1: prompts and tool documentation, Sec. 4.1) through
  * the verification kernels themselves: the sequence [pending token, if any] + tokens is run in
- * passes of up to 1024 rows, each pass as up to 16 consecutive causal chains of 64 rows (a chain's ancestor
+ * passes of up to 2048 rows, each pass as up to 32 consecutive causal chains of 64 rows (a chain's ancestor
  * set is the causal mask; the chains in front of it are part of its context), every row is kept
  * (the K/V of all but the last token are appended to the cache), the last token becomes the
  * pending token.  No logits are produced; the next ts_verify scores the pending token.  Errors (state unchanged): INVALID_ARG, TOKEN_RANGE,

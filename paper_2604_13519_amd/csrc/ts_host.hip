@@ -917,7 +917,7 @@ extern "C" ts_status ts_prefill(ts_model* m, ts_kv* kv, const int32_t* tokens, i
   // is a causal chain (root + 63 nodes: a chain's ancestor set is the causal mask) whose context
   // is everything before it - the committed positions and the blocks in front of it in the same
   // pass, whose K/V the pass writes before any attention launch of the layer reads them.
-  constexpr int kPrefillRows = 64, kPrefillBlocks = 16;
+  constexpr int kPrefillRows = 64, kPrefillBlocks = 32;
   std::vector<int32_t> chain_par((size_t)kPrefillBlocks * (kPrefillRows - 1));
   for (int b = 0; b < kPrefillBlocks; ++b)
     for (int i = 0; i < kPrefillRows - 1; ++i) chain_par[(size_t)b * (kPrefillRows - 1) + i] = i - 1;

@@ -33,7 +33,7 @@ def _oracle_ingest(cfg, omodel, okv, seq, mode):
 
 
 @pytest.mark.parametrize("cfg_name,n_prompt", [("small_fp32", 300), ("small_bf16", 300), ("small_bf16_hd64", 131),
-                                                 ("small_bf16", 1100), ("small_fp32", 577)])
+                                                 ("small_bf16", 1100), ("small_fp32", 577), ("small_bf16", 2300)])
 def test_prefill_cache_matches_causal_forward_and_supports_verify(cfg_name, n_prompt):
     cfg, w, model, omodel = U.get_model(cfg_name)
     fp32 = cfg.dtype == wl.configs.DTYPE_F32
