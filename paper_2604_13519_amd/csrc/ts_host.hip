@@ -144,8 +144,8 @@ static ts_status check_config(const ts_model_config& c) {
     if (c.head_dim != 64 && c.head_dim != 128) return ts_fail(TS_ERR_INVALID_ARG, "bf16 path: head_dim must be 64 or 128");
     if (!is_pow2(c.n_q_heads / c.n_kv_heads)) return ts_fail(TS_ERR_INVALID_ARG, "bf16 path: query heads per KV head must be a power of two");
   } else if (c.dtype == TS_DTYPE_F32) {
-    if (!is_pow2(c.head_dim) || c.head_dim < 2 || c.head_dim > 128)
-      return ts_fail(TS_ERR_INVALID_ARG, "fp32 path: head_dim must be a power of two in [2,128]");
+    if (!is_pow2(c.head_dim) || c.head_dim < 8 || c.head_dim > 128)
+      return ts_fail(TS_ERR_INVALID_ARG, "fp32 path: head_dim must be a power of two in [8,128]");
   } else {
     return ts_fail(TS_ERR_INVALID_ARG, "dtype must be TS_DTYPE_F32 or TS_DTYPE_BF16");
   }
@@ -154,13 +154,13 @@ static ts_status check_config(const ts_model_config& c) {
 
 static void free_workspace(ts_model* m) {
   dev_free(m->H); dev_free(m->Xn); dev_free(m->Qb); dev_free(m->Ab); dev_free(m->Fb); dev_free(m->part);
-  dev_free(m->attn_part_o); dev_free(m->attn_part_ml); dev_free(m->rope_cs); dev_free(m->amax_val);
+  dev_free(m->attn_part_o); dev_free(m->attn_part_ml); dev_free(m->rope_cs); dev_free(m->row_dst); dev_free(m->amax_val);
   dev_free(m->amax_idx); dev_free(m->logits); dev_free(m->meta_dev); dev_free(m->seq_dev);
   dev_free(m->samp_lse); dev_free(m->samp_tok);
   if (m->meta_host) (void)hipHostFree(m->meta_host);
   if (m->res_host) (void)hipHostFree(m->res_host);
   m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr;
-  m->attn_part_o = nullptr; m->attn_part_ml = nullptr; m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr;
+  m->attn_part_o = nullptr; m->attn_part_ml = nullptr; m->rope_cs = nullptr; m->row_dst = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr;
   m->logits = nullptr; m->meta_dev = nullptr; m->seq_dev = nullptr; m->meta_host = nullptr; m->res_host = nullptr;
   m->samp_lse = nullptr; m->samp_tok = nullptr;
   m->ws_rows = 0; m->ws_seqs = 0; m->logits_rows = 0; m->attn_max_splits = 0; m->part_elems = 0;
@@ -206,6 +206,7 @@ static ts_status ensure_workspace(ts_model* m, int rows, int seqs, bool want_log
     m->part_elems = pe;
     if ((st = dev_alloc_bytes((void**)&m->part, pe * 4, true))) return st;
     if ((st = dev_alloc_bytes((void**)&m->rope_cs, (size_t)alloc_rows * (c.head_dim / 2) * sizeof(float2), true))) return st;
+    if ((st = dev_alloc_bytes((void**)&m->row_dst, (size_t)alloc_rows * sizeof(RowDst), true))) return st;
     if ((st = dev_alloc_bytes((void**)&m->amax_val, (size_t)alloc_rows * m->amax_parts * 4, true))) return st;
     if ((st = dev_alloc_bytes((void**)&m->amax_idx, (size_t)alloc_rows * m->amax_parts * 4, true))) return st;
     if ((st = dev_alloc_bytes((void**)&m->samp_lse, (size_t)alloc_rows * 4, true))) return st;
@@ -384,7 +385,7 @@ extern "C" ts_status ts_model_load(const ts_model_config* cfg, const ts_weights*
   m->embed = m->lm_head = nullptr; m->norm_f = nullptr; m->range_flag = nullptr; m->sat_count = nullptr;
   m->H = nullptr; m->Xn = m->Qb = m->Ab = m->Fb = nullptr; m->part = nullptr; m->part_elems = 0;
   m->attn_part_o = nullptr; m->attn_part_ml = nullptr; m->attn_max_splits = 0;
-  m->rope_cs = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr; m->logits = nullptr;
+  m->rope_cs = nullptr; m->row_dst = nullptr; m->amax_val = nullptr; m->amax_idx = nullptr; m->logits = nullptr;
   m->keep_logits = false; m->logits_rows = 0; m->meta_dev = nullptr; m->meta_host = nullptr; m->meta_bytes = 0;
   m->seq_dev = nullptr; m->res_host = nullptr; m->ws_rows = 0; m->ws_seqs = 0;
   m->samp_lse = nullptr; m->samp_tok = nullptr;
@@ -741,8 +742,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
   const bool time_pass = m->prof_on && m->prof_filter == "verify_pass";
   if (time_pass) prof_begin(m, "verify_pass");
   const size_t pass_rec = m->prof.size();
-  launch_embed(m, dm, R);
-  launch_rope_table(m, dm, R);
+  launch_embed(m, dm, R);       // + rotary table and K/V destinations of the rows
   int pending_parts = 0;          // split-K partials of the previous projection still to be added to H
   size_t pending_stride = 0;
   auto project = [&](const char* name, const void* X, const void* W, int N, int K, int* n_parts, size_t* stride) {

@@ -51,6 +51,13 @@ struct SeqDesc {
 };
 constexpr int TS_RESULT_INTS = 4 + 2 * TS_MAX_NODES;
 
+// Where a row's new K and V go (layer 0, KV head 0): written once per pass, read by every layer's QKV epilogue.
+struct RowDst {
+  void* k;                 // K page row of the slot: + layer * layer_stride + g * 16 * hd + dim
+  void* v;                 // V page column of the slot: + layer * layer_stride + g * hd * 16 + dim * 16
+  size_t layer_stride;     // elements per layer of the sequence's pools
+};
+
 struct ProfRec { const char* name; hipEvent_t a, b; };
 
 struct ts_kv {
@@ -99,6 +106,7 @@ struct ts_model {
   float* attn_part_ml;          // [splits][rows][Hq][2]
   int attn_max_splits;
   float2* rope_cs;              // [rows][hd/2] (cos, sin)
+  RowDst* row_dst;              // [rows]
   float* amax_val; int32_t* amax_idx; int amax_parts;   // [rows][parts]
   int amax_used;                // partials per row the last lm_head launch wrote (<= amax_parts)
   float* logits; bool keep_logits; int logits_rows;     // [rows][V] when kept
@@ -121,7 +129,6 @@ struct ts_model {
 void launch_repack_tiles(hipStream_t s, const bf16_t* src, f16_t* dst, int N, int K, int n_tile0, int n_tile_stride,
                          int* range_flag);
 void launch_embed(ts_model* m, const RowMeta& rm, int R);
-void launch_rope_table(ts_model* m, const RowMeta& rm, int R);
 void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part_stride, bool first);
 void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_parts, size_t part_stride);
 void launch_swiglu(ts_model* m, int R, int n_parts, size_t part_stride);

@@ -68,40 +68,61 @@ void launch_repack_tiles(hipStream_t s, const bf16_t* src, f16_t* dst, int N, in
 }
 
 // ---------------------------------------------------------------------------------
-// embedding gather: H[r][:] = E[tok[r]][:]  (residual stream is fp32)
+// Per-row set-up of a pass, one workgroup per row:
+//  * embedding gather H[r][:] = E[tok[r]][:]  (the residual stream is fp32);
+//  * rotary table (cos, sin)(pos[r] * theta^(-2j/hd)) for j < hd/2, evaluated in double so that
+//    large positions lose no phase accuracy, stored as float;
+//  * where the row's K and V go in its sequence's paged cache (layer 0; a layer adds
+//    layer_stride elements), so that the per-layer QKV epilogue needs one load instead of the
+//    chain row -> sequence -> page table.
 // ---------------------------------------------------------------------------------
+__device__ __forceinline__ void widen_store(float* h, const float* e) { *reinterpret_cast<float4*>(h) = *reinterpret_cast<const float4*>(e); }
+__device__ __forceinline__ void widen_store(float* h, const bf16_t* e) {
+  const uint2 v = *reinterpret_cast<const uint2*>(e);             // 4 bf16
+  *reinterpret_cast<float4*>(h) = make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                                               __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+}
+
 template <typename T>
-__global__ void k_embed(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ H, int d) {
+__global__ __launch_bounds__(256) void k_embed_rope(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ H, int d,
+                                                    const int32_t* __restrict__ pos, float2* __restrict__ cs, int half, double theta,
+                                                    const int32_t* __restrict__ row_seq, const int32_t* __restrict__ row_lrow,
+                                                    const SeqDesc* __restrict__ seqs, RowDst* __restrict__ dst, int Hkv) {
   const int r = blockIdx.x;
   const T* e = E + (size_t)tok[r] * d;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) H[(size_t)r * d + i] = ld_f32(e + i);
-}
-
-void launch_embed(ts_model* m, const RowMeta& rm, int R) {
-  ProfScope ps(m, "embed");
-  if (m->cfg.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_embed<bf16_t>, dim3(R), dim3(256), 0, m->stream, (const bf16_t*)m->embed, rm.tok, m->H, m->cfg.d_model);
-  else
-    hipLaunchKernelGGL(k_embed<float>, dim3(R), dim3(256), 0, m->stream, (const float*)m->embed, rm.tok, m->H, m->cfg.d_model);
-}
-
-// ---------------------------------------------------------------------------------
-// rotary table: (cos, sin)(pos[r] * theta^(-2j/hd)) for j < hd/2, evaluated in double so
-// that large positions lose no phase accuracy, stored as float.
-// ---------------------------------------------------------------------------------
-__global__ void k_rope_table(const int32_t* __restrict__ pos, float2* __restrict__ cs, int half, double theta) {
-  const int r = blockIdx.x;
+  if (d % 4 == 0) {
+    for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) widen_store(H + (size_t)r * d + i, e + i);
+  } else {
+    for (int i = threadIdx.x; i < d; i += blockDim.x) H[(size_t)r * d + i] = ld_f32(e + i);
+  }
   for (int j = threadIdx.x; j < half; j += blockDim.x) {
     const double inv_freq = pow(theta, -(double)j / (double)half);
     const double ang = (double)pos[r] * inv_freq;
     cs[(size_t)r * half + j] = make_float2((float)cos(ang), (float)sin(ang));
   }
+  if (threadIdx.x == blockDim.x - 1) {
+    const SeqDesc sd = seqs[row_seq[r]];
+    const int slot = sd.P + row_lrow[r];
+    const int hd = 2 * half;
+    const size_t page_elems = (size_t)Hkv * 16 * hd;
+    const size_t pg = (size_t)sd.page_table[slot >> 4] * page_elems;
+    RowDst o;
+    o.k = (T*)sd.k_pool + pg + (size_t)(slot & 15) * hd;          // + g * 16 * hd + dim
+    o.v = (T*)sd.v_pool + pg + (slot & 15);                        // + g * hd * 16 + dim * 16
+    o.layer_stride = (size_t)sd.n_pages * page_elems;
+    dst[r] = o;
+  }
 }
 
-void launch_rope_table(ts_model* m, const RowMeta& rm, int R) {
-  ProfScope ps(m, "rope_table");
-  hipLaunchKernelGGL(k_rope_table, dim3(R), dim3(64), 0, m->stream, rm.pos, m->rope_cs, m->cfg.head_dim / 2,
-                     (double)m->cfg.rope_theta);
+void launch_embed(ts_model* m, const RowMeta& rm, int R) {
+  ProfScope ps(m, "embed_rope_table");
+  const ts_model_config& c = m->cfg;
+  if (c.dtype == TS_DTYPE_BF16)
+    hipLaunchKernelGGL(k_embed_rope<bf16_t>, dim3(R), dim3(256), 0, m->stream, (const bf16_t*)m->embed, rm.tok, m->H, c.d_model, rm.pos,
+                       m->rope_cs, c.head_dim / 2, (double)c.rope_theta, rm.seq, rm.lrow, m->seq_dev, m->row_dst, c.n_kv_heads);
+  else
+    hipLaunchKernelGGL(k_embed_rope<float>, dim3(R), dim3(256), 0, m->stream, (const float*)m->embed, rm.tok, m->H, c.d_model, rm.pos,
+                       m->rope_cs, c.head_dim / 2, (double)c.rope_theta, rm.seq, rm.lrow, m->seq_dev, m->row_dst, c.n_kv_heads);
 }
 
 // ---------------------------------------------------------------------------------
@@ -183,65 +204,86 @@ void launch_norm(ts_model* m, int R, const float* gain, int n_parts, size_t part
 // the attention kernel and K / V into the row's tree slot (committed length + local row)
 // of its sequence's paged cache.  K pages are [16 tokens][hd]; V pages are stored
 // transposed, [hd][16 tokens], which is the operand order of the P.V product.
+// A workgroup takes one row and 256 / (hd/8) heads; a thread owns the rotation pairs
+// (j .. j+3, j+hd/2 .. j+hd/2+3) of one head: 16-byte loads of every partial, all in flight at once.
+// Needs hd % 8 == 0.
 // ---------------------------------------------------------------------------------
+__device__ __forceinline__ void st_q4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st_q4(bf16_t* p, const float4& v) {
+  *reinterpret_cast<uint2*>(p) = make_uint2((uint32_t)f32_to_f16_bits(v.x) | ((uint32_t)f32_to_f16_bits(v.y) << 16),
+                                            (uint32_t)f32_to_f16_bits(v.z) | ((uint32_t)f32_to_f16_bits(v.w) << 16));
+}
+__device__ __forceinline__ void st_kv4(float* p, const float4& v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st_kv4(bf16_t* p, const float4& v) {
+  *reinterpret_cast<uint2*>(p) = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),
+                                            (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16));
+}
+
 template <typename T>
-__global__ __launch_bounds__(64) void k_rope_kv(const float* __restrict__ part, int n_parts, size_t part_stride,
-                                                const float2* __restrict__ cs, const int32_t* __restrict__ row_seq,
-                                                const int32_t* __restrict__ row_lrow, const SeqDesc* __restrict__ seqs,
-                                                T* __restrict__ Qb, int layer, int Hq, int Hkv, int hd) {
-  const int r = blockIdx.x, head = blockIdx.y;      // heads: Hq query, then Hkv key, then Hkv value
-  const int half = hd / 2;
+__global__ __launch_bounds__(256) void k_rope_kv(const float* __restrict__ part, int n_parts, size_t part_stride,
+                                                 const float2* __restrict__ cs, const RowDst* __restrict__ dst,
+                                                 T* __restrict__ Qb, int layer, int Hq, int Hkv, int hd) {
+  const int r = blockIdx.x;
+  const int half = hd / 2, tph = half / 4;          // threads per head
+  const int head = blockIdx.y * (256 / tph) + threadIdx.x / tph;      // heads: Hq query, then Hkv key, then Hkv value
+  if (head >= Hq + 2 * Hkv) return;
+  const int j = (threadIdx.x % tph) * 4;
   const int q_dim = Hq * hd, N = q_dim + 2 * Hkv * hd;
-  const int j = threadIdx.x;
-  if (j >= half) return;
   const int c1 = head * hd + j, c2 = c1 + half;
+  const RowDst rd = dst[r];
+  const float4 w01 = *reinterpret_cast<const float4*>(cs + (size_t)r * half + j);        // (cos, sin) of j, j+1
+  const float4 w23 = *reinterpret_cast<const float4*>(cs + (size_t)r * half + j + 2);
   const float* p0 = part + (size_t)r * N;
-  float x1 = 0.f, x2 = 0.f;
+  float4 x1 = make_float4(0.f, 0.f, 0.f, 0.f), x2 = x1;
   for (int s0 = 0; s0 < n_parts; s0 += 8) {
-    float a[8], b[8];
+    float4 a[8], b[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const bool ok = s0 + u < n_parts;
-      a[u] = ok ? p0[(size_t)(s0 + u) * part_stride + c1] : 0.f;
-      b[u] = ok ? p0[(size_t)(s0 + u) * part_stride + c2] : 0.f;
+      const int su = min(s0 + u, n_parts - 1);
+      a[u] = *reinterpret_cast<const float4*>(p0 + (size_t)su * part_stride + c1);
+      b[u] = *reinterpret_cast<const float4*>(p0 + (size_t)su * part_stride + c2);
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) { x1 += a[u]; x2 += b[u]; }
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < n_parts) {
+        x1.x += a[u].x; x1.y += a[u].y; x1.z += a[u].z; x1.w += a[u].w;
+        x2.x += b[u].x; x2.y += b[u].y; x2.z += b[u].z; x2.w += b[u].w;
+      }
   }
-  if (head < Hq) {
-    const float2 w = cs[(size_t)r * half + j];
-    st_q(Qb + (size_t)r * q_dim + c1, x1 * w.x - x2 * w.y);
-    st_q(Qb + (size_t)r * q_dim + c2, x2 * w.x + x1 * w.y);
+  if (head >= Hq + Hkv) {                             // V: transposed in-page, [dim][16 tokens]
+    const int g = head - Hq - Hkv;
+    T* vcol = (T*)rd.v + (size_t)layer * rd.layer_stride + (size_t)g * hd * 16;
+    st_from_f32(vcol + (size_t)(j + 0) * 16, x1.x); st_from_f32(vcol + (size_t)(j + 1) * 16, x1.y);
+    st_from_f32(vcol + (size_t)(j + 2) * 16, x1.z); st_from_f32(vcol + (size_t)(j + 3) * 16, x1.w);
+    st_from_f32(vcol + (size_t)(j + half + 0) * 16, x2.x); st_from_f32(vcol + (size_t)(j + half + 1) * 16, x2.y);
+    st_from_f32(vcol + (size_t)(j + half + 2) * 16, x2.z); st_from_f32(vcol + (size_t)(j + half + 3) * 16, x2.w);
     return;
   }
-  const SeqDesc sd = seqs[row_seq[r]];
-  const int slot = sd.P + row_lrow[r];
-  const int t = slot & 15;
-  const size_t page_elems = (size_t)Hkv * 16 * hd;
-  const size_t pg = ((size_t)layer * sd.n_pages + sd.page_table[slot >> 4]) * page_elems;
-  if (head < Hq + Hkv) {
-    const int g = head - Hq;
-    const float2 w = cs[(size_t)r * half + j];
-    T* krow = (T*)sd.k_pool + pg + ((size_t)g * 16 + t) * hd;
-    st_from_f32(krow + j, x1 * w.x - x2 * w.y);
-    st_from_f32(krow + j + half, x2 * w.x + x1 * w.y);
+  const float4 lo = make_float4(x1.x * w01.x - x2.x * w01.y, x1.y * w01.z - x2.y * w01.w,
+                                x1.z * w23.x - x2.z * w23.y, x1.w * w23.z - x2.w * w23.w);
+  const float4 hi = make_float4(x2.x * w01.x + x1.x * w01.y, x2.y * w01.z + x1.y * w01.w,
+                                x2.z * w23.x + x1.z * w23.y, x2.w * w23.z + x1.w * w23.w);
+  if (head < Hq) {
+    st_q4(Qb + (size_t)r * q_dim + c1, lo);
+    st_q4(Qb + (size_t)r * q_dim + c2, hi);
   } else {
-    const int g = head - Hq - Hkv;
-    T* vcol = (T*)sd.v_pool + pg + (size_t)g * hd * 16 + t;
-    st_from_f32(vcol + (size_t)j * 16, x1);
-    st_from_f32(vcol + (size_t)(j + half) * 16, x2);
+    T* krow = (T*)rd.k + (size_t)layer * rd.layer_stride + (size_t)(head - Hq) * 16 * hd;
+    st_kv4(krow + j, lo);
+    st_kv4(krow + j + half, hi);
   }
 }
 
-void launch_rope_kv(ts_model* m, const RowMeta& rm, int R, int layer, int n_parts, size_t part_stride) {
+void launch_rope_kv(ts_model* m, const RowMeta&, int R, int layer, int n_parts, size_t part_stride) {
   ProfScope ps(m, "rope_kv_write");
   const ts_model_config& c = m->cfg;
+  const int heads_per_wg = 256 / (c.head_dim / 8);
+  const dim3 grid(R, (c.n_q_heads + 2 * c.n_kv_heads + heads_per_wg - 1) / heads_per_wg);
   if (c.dtype == TS_DTYPE_BF16)
-    hipLaunchKernelGGL(k_rope_kv<bf16_t>, dim3(R, c.n_q_heads + 2 * c.n_kv_heads), dim3(64), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
-                       rm.seq, rm.lrow, m->seq_dev, (bf16_t*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
+    hipLaunchKernelGGL(k_rope_kv<bf16_t>, grid, dim3(256), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs, m->row_dst,
+                       (bf16_t*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
   else
-    hipLaunchKernelGGL(k_rope_kv<float>, dim3(R, c.n_q_heads + 2 * c.n_kv_heads), dim3(64), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs,
-                       rm.seq, rm.lrow, m->seq_dev, (float*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
+    hipLaunchKernelGGL(k_rope_kv<float>, grid, dim3(256), 0, m->stream, m->part, n_parts, part_stride, m->rope_cs, m->row_dst,
+                       (float*)m->Qb, layer, c.n_q_heads, c.n_kv_heads, c.head_dim);
 }
 
 // ---------------------------------------------------------------------------------
