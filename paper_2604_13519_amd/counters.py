@@ -1,6 +1,6 @@
 """Summaries of rocprofv3 runs over bench.py, written under profiles/.
 
-    python -m paper_2604_13519_amd.counters trace <kernel_trace.db> [--workload w3] [--command "..."]
+    python -m paper_2604_13519_amd.counters trace <kernel_trace.db> [--workload w3] [--command "..."] [--bench line.json]
 
 writes profiles/verify_<workload>_kernel_trace.md: per kernel (the split projections told apart by
 their grids) calls, total and average duration, and the launches, span and gaps of one timed step.
@@ -119,7 +119,7 @@ def sq_summary(dbs, out_path, commit):
     return 0
 
 
-def trace_summary(db, workload, command):
+def trace_summary(db, workload, command, bench_json=None):
     """profiles/verify_<workload>_kernel_trace.md from a --kernel-trace results database."""
     cur = sqlite3.connect(db).cursor()
     rows = list(cur.execute("select name, start, end, grid_x, grid_y, workgroup_x from kernels order by start"))
@@ -159,11 +159,27 @@ def trace_summary(db, workload, command):
             gaps = [(step[i + 1][1] - step[i][2]) / 1e3 for i in range(len(step) - 1)]
             f.write("\nOne step in the middle of the run (row set-up kernel to the last kernel before the next one): %d kernels, span %.1f us, "
                     "busy %.1f us, gaps %.1f us (largest %.2f us).\n" % (len(step), span, busy, sum(g for g in gaps if g > 0), max(gaps)))
+        if bench_json:
+            d = json.loads(open(bench_json).read().strip().splitlines()[-1])
+            rf = d["roofline"]
+            kname = [k for k in agg if _gemm_mode(k.split(" grid ")[0]) == (2 if rf["kernel"] == "gemm_gate_up" else -1) or
+                     (rf["kernel"] == "gemm_gate_up" and k.startswith("k_gemm_rows_bf16") and k.split(",")[-1].startswith(" 2>"))]
+            if kname:
+                n, t = agg[kname[0]]
+                f.write("\nRoofline kernel of bench.py's line for this build (`%s`): trace average %.2f us per launch; bench.py's HIP-event "
+                        "bracket around the same launches reads %.2f us (each bracket carries 2 - 3 us of event overhead), i.e. %s %.0f from the "
+                        "trace against %.0f reported.\n" % (rf["kernel"], t / n, rf["avg_us"], rf["unit"],
+                                                          rf["achieved"] * rf["avg_us"] / (t / n), rf["achieved"]))
     print("wrote", path)
     return 0
 
 
+_COMMIT_OVERRIDE = None      # --commit <hash>: the tree the profiler ran on, when that is not the checked-out one
+
+
 def _commit():
+    if _COMMIT_OVERRIDE:
+        return _COMMIT_OVERRIDE
     try:
         return subprocess.run(["git", "-C", ROOT, "rev-parse", "--short=12", "HEAD"], capture_output=True, text=True).stdout.strip()
     except Exception:
@@ -175,6 +191,9 @@ def main(argv):
         print(__doc__)
         return 2
     workload = argv[argv.index("--workload") + 1] if "--workload" in argv else "w3"
+    if "--commit" in argv:
+        global _COMMIT_OVERRIDE
+        _COMMIT_OVERRIDE = argv[argv.index("--commit") + 1]
     if argv[0] == "sq":
         out = argv[argv.index("--out") + 1] if "--out" in argv else os.path.join(ROOT, "profiles", "verify_mfma_lds_counters.md")
         commit = argv[argv.index("--commit") + 1] if "--commit" in argv else _commit()
@@ -184,7 +203,7 @@ def main(argv):
         command = argv[argv.index("--command") + 1] if "--command" in argv else \
             "rocprofv3 --kernel-trace --stats -d <dir> -o t -- python3 bench.py --steps 8 --warmup 2 --no-cpu-baseline" + \
             ("" if workload == "w3" else " --workload " + workload)
-        return trace_summary(argv[1], workload, command)
+        return trace_summary(argv[1], workload, command, argv[argv.index("--bench") + 1] if "--bench" in argv else None)
     rd, wr = argv[0], argv[1]
     R, W = _load(rd), _load(wr)
     copy_rd = max(R[[k for k in R if "copyBuffer" in k][0]]["TCC_EA0_RDREQ_128B_sum"]) * 128
