@@ -309,6 +309,22 @@ def test_lossless_against_independent_greedy_decoder(cfg_name):
     assert steps < n_out                                   # some drafts were accepted
 
 
+@pytest.mark.parametrize("cfg_name", ["micro_fp32", "small_fp32"])
+def test_greedy_decode_equals_the_independent_decoder(cfg_name):
+    """greedy_decode (verify with an empty tree + commit, repeated) against the dense causal decoder's
+    own greedy continuation: same tokens, cache length advanced by one per token, and the cache equal
+    to a real prefill of the emitted sequence."""
+    cfg, w, model, kv, prompt, rng = _setup(cfg_name, 9)
+    n = 12
+    ref = D.greedy_sequence(cfg, w, prompt, n)
+    P0 = kv.P
+    out = O.greedy_decode(model, kv, n)
+    assert out == ref
+    assert kv.P == P0 + n and kv.pending == ref[-1]
+    _, K, V = D.causal_forward(cfg, w, list(prompt) + ref[:-1], return_kv=True)
+    assert _rel(kv.K[:, :kv.P], K) < 1e-10 and _rel(kv.V[:, :kv.P], V) < 1e-10
+
+
 def test_commit_moves_accepted_rows_and_requires_nothing_else():
     """After commit the cache must equal what a real prefill of the emitted sequence
     would hold (rows moved to positions P+1..P+l, root at P)."""
