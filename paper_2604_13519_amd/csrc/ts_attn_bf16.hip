@@ -48,8 +48,8 @@ struct AttnArgs {
   const bf16_t* Qb;          // [rows][Hq*HD], IEEE half bit patterns
   const uint64_t* row_anc;   // [rows]
   const SeqDesc* seqs;
-  uint16_t* part_o;          // [splits][R][Hq][HD], IEEE half: the split's output divided by its row sum
-  float* part_ml;            // [splits][R][Hq][2]
+  uint16_t* part_o;          // [R][Hq][splits][HD], IEEE half: the split's output divided by its row sum
+  float* part_ml;            // [R][Hq][splits][2]
   int layer, Hq, Hkv, R, splits, n_seqs;
   float scale;               // 1/sqrt(head_dim) * log2(e): scores are kept in log2 units
 };
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(64 * HB * (MT1 > 0 ? 2 : 1), (HB * (MT1 > 0 ? 2 : 1
     const float l = l_run[mt];     // already the sum over all keys (MFMA reduces over the lane groups)
     const int lrow = (tile0 + mt) * 16 + l15;
     if (lrow < M) {
-      const size_t base = ((size_t)split * a.R + sd.row0 + lrow) * a.Hq + h;
+      const size_t base = ((size_t)(sd.row0 + lrow) * a.Hq + h) * a.splits + split;
       if (g4 == 0) {
         a.part_ml[base * 2 + 0] = m_run[mt];
         a.part_ml[base * 2 + 1] = l;
@@ -382,12 +382,11 @@ __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__
   const int tpp = HD / 4;                  // threads per group: four dims of the head each
   const int groups = 256 / tpp;
   const int grp = tid / tpp, d4 = tid % tpp;
-  const size_t n_slots = (size_t)R * Hq;
   const size_t slot = blockIdx.x;
   const float2* ml = reinterpret_cast<const float2*>(part_ml);
   const uint2* po = reinterpret_cast<const uint2*>(part_o);     // 4 halves
   for (int sp = tid; sp < splits; sp += 256) {
-    const float2 v = ml[(size_t)sp * n_slots + slot];
+    const float2 v = ml[slot * splits + sp];
     s_m[sp] = v.x;
     s_l[sp] = v.y;
   }
@@ -395,7 +394,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const int sp = grp + u * groups;
-    o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_uint2(0u, 0u);
+    o4[u] = sp < splits ? po[(slot * splits + sp) * tpp + d4] : make_uint2(0u, 0u);
   }
   __syncthreads();
   float mstar = -INFINITY;
@@ -407,7 +406,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const uint16_t* __restrict__
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int sp = s0 + grp + u * groups;
-        o4[u] = sp < splits ? po[((size_t)sp * n_slots + slot) * tpp + d4] : make_uint2(0u, 0u);
+        o4[u] = sp < splits ? po[(slot * splits + sp) * tpp + d4] : make_uint2(0u, 0u);
       }
     }
 #pragma unroll

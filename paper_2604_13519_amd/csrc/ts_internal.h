@@ -102,8 +102,8 @@ struct ts_model {
   void* Fb;                     // SwiGLU product [rows][F]; float, or IEEE half for bf16 models
   float* part;                  // split-K partial sums, [S][rows][N] fp32
   size_t part_elems;
-  uint16_t* attn_part_o;        // [splits][rows][Hq][hd], IEEE half (each split's normalised output)
-  float* attn_part_ml;          // [splits][rows][Hq][2]
+  uint16_t* attn_part_o;        // [rows][Hq][splits][hd], IEEE half (each split's normalised output)
+  float* attn_part_ml;          // [rows][Hq][splits][2]
   int attn_max_splits;
   float2* rope_cs;              // [rows][hd/2] (cos, sin)
   RowDst* row_dst;              // [rows]
