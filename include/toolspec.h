@@ -52,6 +52,7 @@ extern "C" {
 
 typedef struct ts_model ts_model; /* opaque; owns device weights, workspace, stream */
 typedef struct ts_kv    ts_kv;    /* opaque; owns one sequence's paged K/V          */
+typedef struct ts_kv_pool ts_kv_pool; /* opaque; physical K/V pages shared by several caches */
 typedef int32_t ts_status;
 
 enum {
@@ -154,6 +155,21 @@ ts_status ts_kv_free(ts_kv* kv);
 /* Replace the identity page table by a permutation of [0, n_pages) (n_pages =
  * ceil(capacity/page_size)); only legal while the cache is empty. */
 ts_status ts_kv_set_page_table(ts_kv* kv, const int32_t* phys_page, int32_t n_pages);
+
+/* A pool of physical K/V pages (page = 16 positions of every layer and KV head) that several
+ * caches of one model draw from, so that requests of different lengths share one allocation
+ * (the batched workloads: ragged contexts).  ts_kv_alloc_pooled takes ceil(capacity_tokens / 16)
+ * free pages - whichever are free, in no particular order: a cache's pages are scattered over
+ * the pool - and ts_kv_free gives them back; the page contents are not cleared (positions beyond
+ * a cache's length are never read as data).  Results do not depend on where the pages lie: a
+ * pooled cache gives bit for bit what a cache of its own allocation gives.
+ * Errors: INVALID_ARG; OOM (device allocation, or fewer free pages than the capacity needs - the
+ * pool is then unchanged); STATE (ts_kv_pool_free while caches drawn from the pool are alive;
+ * ts_kv_set_page_table on a pooled cache).  Free the pool BEFORE ts_model_free. */
+ts_status ts_kv_pool_create(ts_model* m, int32_t n_pages, ts_kv_pool** out);
+ts_status ts_kv_pool_free(ts_kv_pool* pool);
+ts_status ts_kv_pool_pages_free(const ts_kv_pool* pool, int32_t* n_free_pages);
+ts_status ts_kv_alloc_pooled(ts_kv_pool* pool, int32_t capacity_tokens, ts_kv** out);
 /* Test/bench helpers: synthetic K/V for contexts whose real prefill the CPU oracle cannot afford.
  * k_host / v_host: [n_layers][n_pos][n_kv_heads][head_dim] in the model dtype,
  * K already rotated.  Import sets the committed length to n_pos. */

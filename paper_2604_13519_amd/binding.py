@@ -21,7 +21,8 @@ TS_Q_OTHERS, TS_Q_TOOL_NAME, TS_Q_PARAM_NAME, TS_Q_PARAM_VALUE = 0, 1, 2, 3
 TS_DRAFT_NONE, TS_DRAFT_RETRIEVAL, TS_DRAFT_SCHEMA = 0, 1, 2
 
 EXPORTS = ("ts_last_error", "ts_model_load", "ts_model_free", "ts_model_keep_logits", "ts_get_logits", "ts_get_row_tokens", "ts_model_saturations", "ts_get_hidden",
-           "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_import", "ts_kv_export", "ts_kv_export_noalloc",
+           "ts_kv_alloc", "ts_kv_free", "ts_kv_set_page_table", "ts_kv_pool_create", "ts_kv_pool_free", "ts_kv_pool_pages_free",
+           "ts_kv_alloc_pooled", "ts_kv_import", "ts_kv_export", "ts_kv_export_noalloc",
            "ts_set_pending", "ts_kv_len", "ts_kv_truncate", "ts_prefill", "ts_verify", "ts_verify_sample", "ts_verify_batch",
            "ts_kv_commit", "ts_profile_enable", "ts_profile_filter", "ts_profile_read", "ts_profile_plain_read",
            "ts_drafter_create", "ts_drafter_free", "ts_drafter_retrieve", "ts_drafter_reset",
@@ -98,6 +99,10 @@ def load_library(path=None):
         "ts_kv_alloc": [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)],
         "ts_kv_free": [C.c_void_p],
         "ts_kv_set_page_table": [C.c_void_p, i32p, C.c_int32],
+        "ts_kv_pool_create": [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)],
+        "ts_kv_pool_free": [C.c_void_p],
+        "ts_kv_pool_pages_free": [C.c_void_p, C.POINTER(C.c_int32)],
+        "ts_kv_alloc_pooled": [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)],
         "ts_kv_import": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
         "ts_kv_export": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
         "ts_kv_export_noalloc": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
@@ -226,6 +231,28 @@ def ts_kv_free(kv):
 def ts_kv_set_page_table(kv, phys_pages):
     p = _i32(phys_pages)
     _check(load_library().ts_kv_set_page_table(kv, _ptr_i32(p), len(p)))
+
+
+def ts_kv_pool_create(model, n_pages):
+    out = C.c_void_p()
+    _check(load_library().ts_kv_pool_create(model, n_pages, C.byref(out)))
+    return out
+
+
+def ts_kv_pool_free(pool):
+    _check(load_library().ts_kv_pool_free(pool))
+
+
+def ts_kv_pool_pages_free(pool):
+    n = C.c_int32()
+    _check(load_library().ts_kv_pool_pages_free(pool, C.byref(n)))
+    return n.value
+
+
+def ts_kv_alloc_pooled(pool, capacity_tokens):
+    out = C.c_void_p()
+    _check(load_library().ts_kv_alloc_pooled(pool, capacity_tokens, C.byref(out)))
+    return out
 
 
 def ts_kv_import(kv, k_host, v_host):

@@ -475,8 +475,58 @@ extern "C" ts_status ts_kv_free(ts_kv* kv) {
   if (!kv) return TS_OK;
   (void)hipSetDevice(kv->model->device);
   (void)hipStreamSynchronize(kv->model->stream);
-  dev_free(kv->k_pool); dev_free(kv->v_pool); dev_free(kv->page_table); dev_free(kv->result);
+  if (kv->pool) {                                   // the pages go back to the pool they came from
+    ts_kv_pool* pool = kv->pool;
+    for (int i = (int)kv->page_table_host.size() - 1; i >= 0; --i) pool->free_pages.push_back(kv->page_table_host[i]);
+    pool->live -= 1;
+  } else {
+    dev_free(kv->k_pool); dev_free(kv->v_pool);
+  }
+  dev_free(kv->page_table); dev_free(kv->result);
   delete kv;
+  return TS_OK;
+}
+
+// A cache over `pages` (physical page numbers within an allocation of pool_pages pages at k_pool / v_pool);
+// pool == nullptr: the allocation is the cache's own and is freed with it.
+static ts_status kv_create(ts_model* m, ts_kv_pool* pool, void* k_pool, void* v_pool, int32_t pool_pages, int32_t capacity,
+                           std::vector<int32_t>&& pages, ts_kv** out) {
+  ts_kv* kv = new (std::nothrow) ts_kv();
+  if (!kv) {
+    if (!pool) { dev_free(k_pool); dev_free(v_pool); }
+    else for (int i = (int)pages.size() - 1; i >= 0; --i) pool->free_pages.push_back(pages[i]);
+    return ts_fail(TS_ERR_OOM, "host allocation failed");
+  }
+  const ts_model_config& c = m->cfg;
+  kv->model = m;
+  kv->pool = pool;
+  kv->capacity = capacity;
+  kv->page_size = TS_PAGE_SIZE;
+  kv->n_pages = (int32_t)pages.size();
+  kv->pool_pages = pool_pages;
+  kv->P = 0;
+  kv->pending = -1;
+  kv->have_result = false;
+  kv->last_M = 0;
+  kv->k_pool = k_pool; kv->v_pool = v_pool; kv->page_table = nullptr; kv->result = nullptr;
+  kv->layer_stride_elems = (size_t)pool_pages * c.n_kv_heads * 16 * c.head_dim;
+  kv->page_table_host = std::move(pages);
+  // the attention kernel fetches the table four entries (one key block) at a time: pad with page 0
+  ts_status st = dev_alloc_bytes((void**)&kv->page_table, (size_t)(kv->n_pages + 4) * 4, true);
+  if (!st) st = dev_alloc_bytes((void**)&kv->result, TS_RESULT_INTS * 4, true);
+  if (!st) {
+    hipError_t e = copy_sync(m->stream, kv->page_table, kv->page_table_host.data(), (size_t)kv->n_pages * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) st = ts_fail(TS_ERR_DEVICE, "page table upload failed: %s", hipGetErrorString(e));
+  }
+  if (st) {
+    std::string keep = g_last_error;
+    if (pool) pool->live += 1;          // ts_kv_free gives the pages back and counts the cache out again
+    ts_kv_free(kv);
+    g_last_error = keep;
+    return st;
+  }
+  if (pool) pool->live += 1;
+  *out = kv;
   return TS_OK;
 }
 
@@ -486,43 +536,75 @@ extern "C" ts_status ts_kv_alloc(ts_model* m, int32_t capacity, int32_t page_siz
   if (page_size != TS_PAGE_SIZE) return ts_fail(TS_ERR_INVALID_ARG, "page_size must be %d", TS_PAGE_SIZE);
   if (capacity < 1) return ts_fail(TS_ERR_INVALID_ARG, "capacity_tokens must be positive");
   (void)hipSetDevice(m->device);
-  ts_kv* kv = new (std::nothrow) ts_kv();
-  if (!kv) return ts_fail(TS_ERR_OOM, "host allocation failed");
   const ts_model_config& c = m->cfg;
-  kv->model = m;
-  kv->capacity = capacity;
-  kv->page_size = page_size;
-  kv->n_pages = (capacity + page_size - 1) / page_size;
-  kv->P = 0;
-  kv->pending = -1;
-  kv->have_result = false;
-  kv->last_M = 0;
-  kv->k_pool = kv->v_pool = nullptr; kv->page_table = nullptr; kv->result = nullptr;
-  kv->layer_stride_elems = (size_t)kv->n_pages * c.n_kv_heads * 16 * c.head_dim;
-  const size_t bytes = kv->layer_stride_elems * c.n_layers * m->esz;
-  ts_status st = dev_alloc_bytes(&kv->k_pool, bytes, true);
-  if (!st) st = dev_alloc_bytes(&kv->v_pool, bytes, true);
-  // the attention kernel fetches the table four entries (one key block) at a time: pad with page 0
-  if (!st) st = dev_alloc_bytes((void**)&kv->page_table, (size_t)(kv->n_pages + 4) * 4, true);
-  if (!st) st = dev_alloc_bytes((void**)&kv->result, TS_RESULT_INTS * 4, true);
-  if (!st) {
-    kv->page_table_host.resize(kv->n_pages);
-    for (int i = 0; i < kv->n_pages; ++i) kv->page_table_host[i] = i;
-    hipError_t e = copy_sync(m->stream, kv->page_table, kv->page_table_host.data(), (size_t)kv->n_pages * 4, hipMemcpyHostToDevice);
-    if (e != hipSuccess) st = ts_fail(TS_ERR_DEVICE, "page table upload failed: %s", hipGetErrorString(e));
-  }
-  if (st) {
-    std::string keep = g_last_error;
-    ts_kv_free(kv);
-    g_last_error = keep;
-    return st;
-  }
-  *out = kv;
+  const int32_t n_pages = (capacity + page_size - 1) / page_size;
+  const size_t bytes = (size_t)n_pages * c.n_kv_heads * 16 * c.head_dim * c.n_layers * m->esz;
+  void* k_pool = nullptr; void* v_pool = nullptr;
+  ts_status st = dev_alloc_bytes(&k_pool, bytes, true);
+  if (!st) st = dev_alloc_bytes(&v_pool, bytes, true);
+  if (st) { dev_free(k_pool); dev_free(v_pool); return st; }
+  std::vector<int32_t> pages(n_pages);
+  for (int i = 0; i < n_pages; ++i) pages[i] = i;
+  return kv_create(m, nullptr, k_pool, v_pool, n_pages, capacity, std::move(pages), out);
+}
+
+// ---------------------------------------------------------------------------------
+// shared page pool
+// ---------------------------------------------------------------------------------
+extern "C" ts_status ts_kv_pool_create(ts_model* m, int32_t n_pages, ts_kv_pool** out) {
+  if (!m || !out) return ts_fail(TS_ERR_INVALID_ARG, "ts_kv_pool_create: null argument");
+  *out = nullptr;
+  if (n_pages < 1) return ts_fail(TS_ERR_INVALID_ARG, "n_pages must be positive");
+  (void)hipSetDevice(m->device);
+  ts_kv_pool* pool = new (std::nothrow) ts_kv_pool();
+  if (!pool) return ts_fail(TS_ERR_OOM, "host allocation failed");
+  const ts_model_config& c = m->cfg;
+  pool->model = m;
+  pool->n_pages = n_pages;
+  pool->k_pool = pool->v_pool = nullptr;
+  pool->live = 0;
+  const size_t bytes = (size_t)n_pages * c.n_kv_heads * 16 * c.head_dim * c.n_layers * m->esz;
+  ts_status st = dev_alloc_bytes(&pool->k_pool, bytes, true);
+  if (!st) st = dev_alloc_bytes(&pool->v_pool, bytes, true);
+  if (st) { dev_free(pool->k_pool); dev_free(pool->v_pool); delete pool; return st; }
+  pool->free_pages.resize(n_pages);
+  for (int i = 0; i < n_pages; ++i) pool->free_pages[i] = n_pages - 1 - i;      // page 0 is handed out first
+  *out = pool;
   return TS_OK;
+}
+
+extern "C" ts_status ts_kv_pool_free(ts_kv_pool* pool) {
+  if (!pool) return TS_OK;
+  if (pool->live != 0) return ts_fail(TS_ERR_STATE, "%d caches drawn from the pool are still alive", pool->live);
+  (void)hipSetDevice(pool->model->device);
+  (void)hipStreamSynchronize(pool->model->stream);
+  dev_free(pool->k_pool); dev_free(pool->v_pool);
+  delete pool;
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_pool_pages_free(const ts_kv_pool* pool, int32_t* n_free_pages) {
+  if (!pool || !n_free_pages) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  *n_free_pages = (int32_t)pool->free_pages.size();
+  return TS_OK;
+}
+
+extern "C" ts_status ts_kv_alloc_pooled(ts_kv_pool* pool, int32_t capacity, ts_kv** out) {
+  if (!pool || !out) return ts_fail(TS_ERR_INVALID_ARG, "ts_kv_alloc_pooled: null argument");
+  *out = nullptr;
+  if (capacity < 1) return ts_fail(TS_ERR_INVALID_ARG, "capacity_tokens must be positive");
+  const int32_t need = (capacity + TS_PAGE_SIZE - 1) / TS_PAGE_SIZE;
+  if ((size_t)need > pool->free_pages.size())
+    return ts_fail(TS_ERR_OOM, "the pool has %d free pages, capacity %d needs %d", (int)pool->free_pages.size(), capacity, need);
+  (void)hipSetDevice(pool->model->device);
+  std::vector<int32_t> pages(need);
+  for (int i = 0; i < need; ++i) { pages[i] = pool->free_pages.back(); pool->free_pages.pop_back(); }
+  return kv_create(pool->model, pool, pool->k_pool, pool->v_pool, pool->n_pages, capacity, std::move(pages), out);
 }
 
 extern "C" ts_status ts_kv_set_page_table(ts_kv* kv, const int32_t* phys, int32_t n_pages) {
   if (!kv || !phys) return ts_fail(TS_ERR_INVALID_ARG, "null argument");
+  if (kv->pool) return ts_fail(TS_ERR_STATE, "the pages of a pooled cache are assigned by its pool");
   if (kv->P != 0) return ts_fail(TS_ERR_STATE, "page table can only change while the cache is empty");
   if (n_pages != kv->n_pages) return ts_fail(TS_ERR_INVALID_ARG, "n_pages must be %d", kv->n_pages);
   std::vector<char> seen(n_pages, 0);
@@ -726,7 +808,7 @@ static ts_status verify_impl(ts_model* m, ts_kv* const* kvs, int n_seqs, const i
       hm.u[r] = sample ? sample->node_uniform[offs[s] + i] : 0.f;
     }
     SeqDesc& sd = hseq[s];
-    sd.P = P_s; sd.M = n + 1; sd.row0 = r0; sd.n_pages = kv->n_pages;
+    sd.P = P_s; sd.M = n + 1; sd.row0 = r0; sd.n_pages = kv->pool_pages;
     sd.page_table = kv->page_table; sd.k_pool = kv->k_pool; sd.v_pool = kv->v_pool; sd.result = kv->result;
     kv->have_result = false;
     r0 += n + 1;

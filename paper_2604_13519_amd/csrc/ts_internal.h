@@ -43,7 +43,7 @@ struct SeqDesc {
   int32_t P;             // committed length
   int32_t M;             // rows of this sequence (n_nodes + 1)
   int32_t row0;          // first row in the concatenated batch
-  int32_t n_pages;       // logical pages of the cache
+  int32_t n_pages;       // physical pages of the pool the cache's pages live in (the layer stride)
   const int32_t* page_table;   // device, logical page -> physical page
   void* k_pool;          // device, K pages  [L][n_pages][Hkv][16][hd]
   void* v_pool;          // device, V pages  [L][n_pages][Hkv][hd][16]  (transposed in-page)
@@ -60,9 +60,20 @@ struct RowDst {
 
 struct ProfRec { const char* name; hipEvent_t a, b; };
 
+// Physical pages shared by several caches (ts_kv_pool_create)
+struct ts_kv_pool {
+  ts_model* model;
+  int32_t n_pages;
+  void* k_pool; void* v_pool;      // device, [L][n_pages][Hkv][16][hd] / [L][n_pages][Hkv][hd][16]
+  std::vector<int32_t> free_pages; // stack of free physical pages
+  int32_t live;                    // caches drawn from the pool and not yet freed
+};
+
 struct ts_kv {
   ts_model* model;
+  ts_kv_pool* pool;        // nullptr: the cache owns its pages
   int32_t capacity, page_size, n_pages;
+  int32_t pool_pages;      // physical pages of the allocation the pages live in (= n_pages for an own allocation): the layer stride
   int32_t P;               // committed length
   int32_t pending;         // -1 = none
   bool have_result;        // an unapplied verify result exists

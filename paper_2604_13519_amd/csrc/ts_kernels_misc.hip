@@ -588,10 +588,10 @@ void launch_commit(ts_kv* kv, int accept_len) {
   dim3 grid(c.n_layers * c.n_kv_heads), block(c.head_dim <= 64 ? 64 : 128);
   if (c.dtype == TS_DTYPE_BF16)
     hipLaunchKernelGGL(k_commit<bf16_t>, grid, block, 0, m->stream, (bf16_t*)kv->k_pool, (bf16_t*)kv->v_pool,
-                       kv->page_table, kv->result, kv->n_pages, c.n_kv_heads, c.head_dim, kv->P, accept_len);
+                       kv->page_table, kv->result, kv->pool_pages, c.n_kv_heads, c.head_dim, kv->P, accept_len);
   else
     hipLaunchKernelGGL(k_commit<float>, grid, block, 0, m->stream, (float*)kv->k_pool, (float*)kv->v_pool,
-                       kv->page_table, kv->result, kv->n_pages, c.n_kv_heads, c.head_dim, kv->P, accept_len);
+                       kv->page_table, kv->result, kv->pool_pages, c.n_kv_heads, c.head_dim, kv->P, accept_len);
 }
 
 // ---------------------------------------------------------------------------------
@@ -627,11 +627,11 @@ static void kv_xfer(ts_kv* kv, int pos0, int n_pos, void* sk, void* sv, int laye
   if (blocks < 1) blocks = 1;
   if (c.dtype == TS_DTYPE_BF16)
     hipLaunchKernelGGL((k_kv_xfer<bf16_t, IMPORT>), dim3(blocks), dim3(256), 0, m->stream, (bf16_t*)kv->k_pool,
-                       (bf16_t*)kv->v_pool, kv->page_table, (bf16_t*)sk, (bf16_t*)sv, layer, kv->n_pages,
+                       (bf16_t*)kv->v_pool, kv->page_table, (bf16_t*)sk, (bf16_t*)sv, layer, kv->pool_pages,
                        c.n_kv_heads, c.head_dim, pos0, n_pos);
   else
     hipLaunchKernelGGL((k_kv_xfer<float, IMPORT>), dim3(blocks), dim3(256), 0, m->stream, (float*)kv->k_pool,
-                       (float*)kv->v_pool, kv->page_table, (float*)sk, (float*)sv, layer, kv->n_pages, c.n_kv_heads,
+                       (float*)kv->v_pool, kv->page_table, (float*)sk, (float*)sv, layer, kv->pool_pages, c.n_kv_heads,
                        c.head_dim, pos0, n_pos);
 }
 
